@@ -1,0 +1,439 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test is chosen so that a plausible mistake in oracle/kunlun_oracle.c (a dropped term,
+a wrong sign or index, a transposed operand, an off-by-one window edge, a missing scale)
+fails at least one of them:
+  - hand-worked values (tests/golden/hand_worked.txt),
+  - per-query brute force in numpy written independently of the C loops,
+  - library routines: scipy erf / normal cdf, torch fp64 scaled_dot_product_attention,
+    torch fp64 autograd,
+  - closed forms and invariants that the equations imply,
+  - central finite differences for the gradients.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+import torch
+
+from paper_2602_10016_amd import workloads as W
+
+ACTS = {"softmax": 0, "identity": 1, "relu": 2, "gelu": 3, "gelu_tanh": 4, "silu": 5}
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked.txt")
+
+
+# ---------- independent numpy brute force (per-query loops) ----------
+
+def np_act(name, x):
+    if name == "identity":
+        return x
+    if name == "relu":
+        return np.where(x > 0, x, 0.0)
+    if name == "gelu":
+        return x * scipy.stats.norm.cdf(x)
+    if name == "gelu_tanh":
+        return 0.5 * x * (1 + np.tanh(math.sqrt(2 / math.pi) * (x + 0.044715 * x ** 3)))
+    if name == "silu":
+        return x * scipy.special.expit(x)
+    raise KeyError(name)
+
+
+def brute_forward(q, k, v, q_off, kv_off, scale, acts, window=None):
+    """acts: one activation name per head.  window=(left,right) or None."""
+    H = q.shape[1]
+    o = np.zeros_like(q)
+    lse = np.full((H, q.shape[0]), -np.inf)
+    for b in range(len(kv_off) - 1):
+        keys = slice(kv_off[b], kv_off[b + 1])
+        n = kv_off[b + 1] - kv_off[b]
+        for row in range(q_off[b], q_off[b + 1]):
+            t = row - q_off[b]
+            idx = np.arange(n)
+            if window is not None:
+                left, right = window
+                keep = np.ones(n, dtype=bool)
+                if left >= 0:
+                    keep &= idx >= t - left
+                if right >= 0:
+                    keep &= idx <= t + right
+                idx = idx[keep]
+            for h in range(H):
+                if idx.size == 0:
+                    continue
+                kk, vv = k[keys, h][idx], v[keys, h][idx]
+                s = scale * (kk @ q[row, h])
+                if acts[h] == "softmax":
+                    lse[h, row] = scipy.special.logsumexp(s)
+                    o[row, h] = scipy.special.softmax(s) @ vv
+                else:
+                    lse[h, row] = 0.0
+                    o[row, h] = np_act(acts[h], s) @ vv
+    return o, lse
+
+
+def rand_problem(rng, lens_q, lens_kv, H, d, sigma=1.0):
+    q_off = W.offsets_from_lengths(lens_q)
+    kv_off = W.offsets_from_lengths(lens_kv)
+    q = rng.standard_normal((q_off[-1], H, d)) * sigma
+    k = rng.standard_normal((kv_off[-1], H, d)) * sigma
+    v = rng.standard_normal((kv_off[-1], H, d)) * sigma
+    return q, k, v, q_off, kv_off
+
+
+# ---------- hand-worked values ----------
+
+def _golden_cases():
+    cases = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, act, scale, qrow, krows, vrows, orow = [c.strip() for c in line.split("|")]
+            mat = lambda s: np.array([[float(x) for x in r.split()] for r in s.split(";")])
+            cases.append(pytest.param(act, float(scale), mat(qrow), mat(krows), mat(vrows), mat(orow), id=name))
+    return cases
+
+
+@pytest.mark.parametrize("act,scale,q,k,v,o_expected", _golden_cases())
+def test_hand_worked(oracle, act, scale, q, k, v, o_expected):
+    o, _ = oracle.gdpa_fwd(q[:, None, :], k[:, None, :], v[:, None, :], [0, k.shape[0]], scale, ACTS[act], max_q=1)
+    np.testing.assert_allclose(o[:, 0, :], o_expected, rtol=1e-14, atol=1e-14)
+
+
+# ---------- activations against library routines ----------
+
+@pytest.mark.parametrize("x", [-6.0, -2.5, -1.0, -0.3, 0.0, 1e-3, 0.7, 1.0, 2.0, 5.5])
+def test_activation_values_vs_libraries(oracle, x):
+    t = torch.tensor(x, dtype=torch.float64)
+    assert oracle.act_value(ACTS["gelu"], x) == pytest.approx(x * scipy.stats.norm.cdf(x), rel=1e-13, abs=1e-15)
+    assert oracle.act_value(ACTS["gelu"], x) == pytest.approx(torch.nn.functional.gelu(t).item(), rel=1e-12, abs=1e-15)
+    assert oracle.act_value(ACTS["gelu_tanh"], x) == pytest.approx(
+        torch.nn.functional.gelu(t, approximate="tanh").item(), rel=1e-12, abs=1e-15)
+    assert oracle.act_value(ACTS["silu"], x) == pytest.approx(torch.nn.functional.silu(t).item(), rel=1e-12, abs=1e-15)
+    assert oracle.act_value(ACTS["relu"], x) == max(x, 0.0)
+    assert oracle.act_value(ACTS["identity"], x) == x
+
+
+@pytest.mark.parametrize("name", ["identity", "relu", "gelu", "gelu_tanh", "silu"])
+@pytest.mark.parametrize("x", [-4.0, -1.2, -0.1, 0.4, 1.0, 3.3])
+def test_activation_derivatives_vs_autograd(oracle, name, x):
+    t = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    f = {"identity": lambda z: z, "relu": torch.relu, "gelu": torch.nn.functional.gelu,
+         "gelu_tanh": lambda z: torch.nn.functional.gelu(z, approximate="tanh"),
+         "silu": torch.nn.functional.silu}[name]
+    f(t).backward()
+    assert oracle.act_deriv(ACTS[name], x) == pytest.approx(t.grad.item(), rel=1e-12, abs=1e-14)
+
+
+def test_known_constants(oracle):
+    # Phi(1) = 0.8413447460685429..., logistic(1) = 0.7310585786300049 (standard tables)
+    assert oracle.act_value(ACTS["gelu"], 1.0) == pytest.approx(0.8413447460685429, rel=1e-14)
+    assert oracle.act_value(ACTS["silu"], 1.0) == pytest.approx(0.7310585786300049, rel=1e-14)
+    assert oracle.act_value(ACTS["gelu"], 0.0) == 0.0 and oracle.act_value(ACTS["silu"], 0.0) == 0.0
+
+
+# ---------- brute force on tiny jagged inputs ----------
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("act", list(ACTS))
+def test_gdpa_forward_vs_bruteforce(oracle, seed, act):
+    rng = np.random.default_rng(100 + seed)
+    lens_kv = [5, 0, 1, 9, 3]
+    lens_q = [2, 3, 1, 0, 4]
+    H, d = 3, [4, 7, 8][seed]
+    q, k, v, q_off, kv_off = rand_problem(rng, lens_q, lens_kv, H, d)
+    scale = 0.37
+    o, lse = oracle.gdpa_fwd(q, k, v, kv_off, scale, ACTS[act], q_offsets=q_off)
+    o_ref, lse_ref = brute_forward(q, k, v, q_off, kv_off, scale, [act] * H)
+    np.testing.assert_allclose(o, o_ref, rtol=1e-12, atol=1e-13)
+    if act == "softmax":
+        np.testing.assert_allclose(lse, lse_ref, rtol=1e-12, atol=1e-13)
+        assert np.all(np.isneginf(lse[:, q_off[1]:q_off[2]]))  # example with no keys
+    assert np.all(o[q_off[1]:q_off[2]] == 0.0)
+
+
+def test_gdpa_forward_dense_q_and_per_head_activation(oracle):
+    rng = np.random.default_rng(7)
+    B, Nq, H, d = 4, 3, 6, 5
+    lens_kv = [4, 1, 6, 2]
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * B, lens_kv, H, d)
+    names = ["gelu", "softmax", "relu", "silu", "identity", "gelu_tanh"]
+    o, lse = oracle.gdpa_fwd(q, k, v, kv_off, 0.5, 0, max_q=Nq, head_act=[ACTS[n] for n in names])
+    o_ref, lse_ref = brute_forward(q, k, v, q_off, kv_off, 0.5, names)
+    np.testing.assert_allclose(o, o_ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse[1], lse_ref[1], rtol=1e-12)
+
+
+@pytest.mark.parametrize("window", [(0, 0), (2, 0), (0, 3), (2, 2), (1, 4), (100, 0), (100, 100), (-1, 0), (-1, -1), (3, -1)])
+def test_swa_forward_vs_bruteforce(oracle, window):
+    rng = np.random.default_rng(11)
+    lens = [7, 1, 0, 12, 4]
+    H, d = 2, 6
+    q, k, v, off, _ = rand_problem(rng, lens, lens, H, d)
+    o, lse = oracle.swa_fwd(q, k, v, off, window[0], window[1], 0.41)
+    o_ref, lse_ref = brute_forward(q, k, v, off, off, 0.41, ["softmax"] * H, window=window)
+    np.testing.assert_allclose(o, o_ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(lse, lse_ref, rtol=1e-12, atol=1e-13)
+
+
+# ---------- closed forms ----------
+
+def test_identity_activation_reassociates(oracle):
+    """Act = identity: O = scale * Q (K^T V), computed in the other association order."""
+    rng = np.random.default_rng(3)
+    lens_kv, Nq, H, d = [6, 11, 2], 4, 2, 5
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * 3, lens_kv, H, d)
+    o, _ = oracle.gdpa_fwd(q, k, v, kv_off, 0.125, ACTS["identity"], max_q=Nq)
+    for b in range(3):
+        for h in range(H):
+            ktv = k[kv_off[b]:kv_off[b + 1], h].T @ v[kv_off[b]:kv_off[b + 1], h]
+            np.testing.assert_allclose(o[b * Nq:(b + 1) * Nq, h], 0.125 * q[b * Nq:(b + 1) * Nq, h] @ ktv,
+                                       rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("act", list(ACTS))
+def test_linear_in_v(oracle, act):
+    rng = np.random.default_rng(5)
+    q, k, v, q_off, kv_off = rand_problem(rng, [3, 3], [5, 8], 2, 4)
+    v2 = rng.standard_normal(v.shape)
+    f = lambda vv: oracle.gdpa_fwd(q, k, vv, kv_off, 0.3, ACTS[act], max_q=3)[0]
+    np.testing.assert_allclose(f(v + v2), f(v) + f(v2), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(f(-2.5 * v), -2.5 * f(v), rtol=1e-12, atol=1e-13)
+
+
+def test_softmax_special_cases(oracle):
+    rng = np.random.default_rng(6)
+    q, k, v, q_off, kv_off = rand_problem(rng, [2, 2, 2], [1, 6, 9], 2, 4)
+    # K = 0: uniform weights, O = mean of V over the example, LSE = log(n)
+    o, lse = oracle.gdpa_fwd(q, np.zeros_like(k), v, kv_off, 0.7, ACTS["softmax"], max_q=2)
+    for b, n in enumerate([1, 6, 9]):
+        mean_v = v[kv_off[b]:kv_off[b + 1]].mean(axis=0)
+        np.testing.assert_allclose(o[2 * b], mean_v, rtol=1e-13, atol=1e-14)
+        np.testing.assert_allclose(lse[:, 2 * b], math.log(n), rtol=1e-13, atol=1e-14)
+    # single key: O = v (example 0)
+    o, _ = oracle.gdpa_fwd(q, k, v, kv_off, 0.7, ACTS["softmax"], max_q=2)
+    np.testing.assert_allclose(o[0], v[0], rtol=1e-14)
+    # shift invariance: adding the same vector c to every key adds q.c to every score of a query
+    c = rng.standard_normal((1, 2, 4))
+    o_shift, lse_shift = oracle.gdpa_fwd(q, k + c, v, kv_off, 0.7, ACTS["softmax"], max_q=2)
+    np.testing.assert_allclose(o_shift, o, rtol=1e-11, atol=1e-12)
+    # very large scores must not overflow
+    o_big, lse_big = oracle.gdpa_fwd(q * 1e3, k * 1e3, v, kv_off, 1.0, ACTS["softmax"], max_q=2)
+    assert np.all(np.isfinite(o_big)) and np.all(np.isfinite(lse_big))
+
+
+def test_activation_zero_cases(oracle):
+    rng = np.random.default_rng(8)
+    q, k, v, q_off, kv_off = rand_problem(rng, [2, 2], [4, 7], 2, 3)
+    for act in ["gelu", "gelu_tanh", "silu", "relu", "identity"]:
+        o, _ = oracle.gdpa_fwd(q, np.zeros_like(k), v, kv_off, 1.0, ACTS[act], max_q=2)
+        assert np.all(o == 0.0), act
+    # relu with every score negative: k = -q direction
+    qq = np.abs(q) + 0.1
+    kk = -np.abs(k) - 0.1
+    o, _ = oracle.gdpa_fwd(qq, kk, v, kv_off, 1.0, ACTS["relu"], max_q=2)
+    assert np.all(o == 0.0)
+
+
+def test_window_special_cases(oracle):
+    rng = np.random.default_rng(9)
+    lens = [5, 9, 1]
+    q, k, v, off, _ = rand_problem(rng, lens, lens, 2, 4)
+    # window (0, 0): each token sees only itself
+    o, lse = oracle.swa_fwd(q, k, v, off, 0, 0, 0.5)
+    np.testing.assert_allclose(o, v, rtol=1e-14)
+    # K = 0: output is the windowed mean of V, which checks the key set exactly
+    left, right = 2, 1
+    o, lse = oracle.swa_fwd(q, np.zeros_like(k), v, off, left, right, 0.5)
+    for b, L in enumerate(lens):
+        for t in range(L):
+            lo, hi = max(0, t - left), min(L - 1, t + right)
+            np.testing.assert_allclose(o[off[b] + t], v[off[b] + lo:off[b] + hi + 1].mean(axis=0), rtol=1e-13,
+                                       atol=1e-14)
+            np.testing.assert_allclose(lse[:, off[b] + t], math.log(hi - lo + 1), rtol=1e-13, atol=1e-14)
+
+
+def _sdpa(q, k, v, scale, causal):
+    """torch fp64 library attention on one dense sequence [L, H, d]."""
+    tq, tk, tv = [torch.from_numpy(np.ascontiguousarray(x)).permute(1, 0, 2)[None] for x in (q, k, v)]
+    out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal, scale=scale)
+    return out[0].permute(1, 0, 2).numpy()
+
+
+def test_window_at_least_length_is_full_attention(oracle):
+    rng = np.random.default_rng(10)
+    lens = [6, 13]
+    q, k, v, off, _ = rand_problem(rng, lens, lens, 2, 8)
+    scale = 1 / math.sqrt(8)
+    o_full, _ = oracle.swa_fwd(q, k, v, off, 12, 12, scale)
+    o_unb, _ = oracle.swa_fwd(q, k, v, off, -1, -1, scale)
+    o_causal, _ = oracle.swa_fwd(q, k, v, off, 12, 0, scale)
+    o_gdpa, _ = oracle.gdpa_fwd(q, k, v, off, scale, ACTS["softmax"], q_offsets=off)
+    for b in range(2):
+        s = slice(off[b], off[b + 1])
+        np.testing.assert_allclose(o_full[s], _sdpa(q[s], k[s], v[s], scale, False), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(o_causal[s], _sdpa(q[s], k[s], v[s], scale, True), rtol=1e-12, atol=1e-13)
+    np.testing.assert_array_equal(o_full, o_unb)
+    np.testing.assert_array_equal(o_full, o_gdpa)
+
+
+def test_dense_equal_lengths_match_library_attention_and_autograd(oracle):
+    rng = np.random.default_rng(12)
+    B, Nq, L, H, d = 3, 4, 7, 2, 8
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * B, [L] * B, H, d)
+    d_o = rng.standard_normal(q.shape)
+    scale = 0.3
+    tq = torch.from_numpy(q).reshape(B, Nq, H, d).permute(0, 2, 1, 3).requires_grad_(True)
+    tk = torch.from_numpy(k).reshape(B, L, H, d).permute(0, 2, 1, 3).requires_grad_(True)
+    tv = torch.from_numpy(v).reshape(B, L, H, d).permute(0, 2, 1, 3).requires_grad_(True)
+    out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=scale)
+    tdo = torch.from_numpy(d_o).reshape(B, Nq, H, d).permute(0, 2, 1, 3)
+    (out * tdo).sum().backward()
+    back = lambda t, n: t.permute(0, 2, 1, 3).reshape(B * n, H, d).detach().numpy()
+    o, lse = oracle.gdpa_fwd(q, k, v, kv_off, scale, ACTS["softmax"], max_q=Nq)
+    np.testing.assert_allclose(o, back(out, Nq), rtol=1e-12, atol=1e-13)
+    dq, dk, dv = oracle.gdpa_bwd(q, k, v, d_o, kv_off, scale, ACTS["softmax"], max_q=Nq)
+    np.testing.assert_allclose(dq, back(tq.grad, Nq), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dk, back(tk.grad, L), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dv, back(tv.grad, L), rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("act", ["identity", "relu", "gelu", "gelu_tanh", "silu"])
+def test_activation_mode_backward_vs_autograd(oracle, act):
+    """Jagged, per example: torch fp64 autograd through library activations."""
+    rng = np.random.default_rng(13)
+    lens_q, lens_kv, H, d = [3, 1, 4], [5, 8, 2], 2, 6
+    q, k, v, q_off, kv_off = rand_problem(rng, lens_q, lens_kv, H, d)
+    d_o = rng.standard_normal(q.shape)
+    scale = 0.45
+    f = {"identity": lambda z: z, "relu": torch.relu, "gelu": torch.nn.functional.gelu,
+         "gelu_tanh": lambda z: torch.nn.functional.gelu(z, approximate="tanh"),
+         "silu": torch.nn.functional.silu}[act]
+    dq, dk, dv = oracle.gdpa_bwd(q, k, v, d_o, kv_off, scale, ACTS[act], q_offsets=q_off)
+    for b in range(3):
+        qs, ks = slice(q_off[b], q_off[b + 1]), slice(kv_off[b], kv_off[b + 1])
+        tq = torch.from_numpy(q[qs]).requires_grad_(True)
+        tk = torch.from_numpy(k[ks]).requires_grad_(True)
+        tv = torch.from_numpy(v[ks]).requires_grad_(True)
+        s = torch.einsum("ihc,jhc->hij", tq, tk) * scale
+        out = torch.einsum("hij,jhc->ihc", f(s), tv)
+        (out * torch.from_numpy(d_o[qs])).sum().backward()
+        np.testing.assert_allclose(dq[qs], tq.grad.numpy(), rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(dk[ks], tk.grad.numpy(), rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(dv[ks], tv.grad.numpy(), rtol=1e-11, atol=1e-12)
+
+
+# ---------- finite differences ----------
+
+def _fd_check(fwd, grads, tensors, d_o, eps=1e-6, n_probe=24, seed=0):
+    rng = np.random.default_rng(seed)
+    for which, g in enumerate(grads):
+        x = tensors[which]
+        for _ in range(n_probe):
+            idx = tuple(rng.integers(0, s) for s in x.shape)
+            old = x[idx]
+            x[idx] = old + eps
+            fp = float((fwd(*tensors) * d_o).sum())
+            x[idx] = old - eps
+            fm = float((fwd(*tensors) * d_o).sum())
+            x[idx] = old
+            fd = (fp - fm) / (2 * eps)
+            assert g[idx] == pytest.approx(fd, rel=2e-6, abs=2e-8), (which, idx)
+
+
+@pytest.mark.parametrize("act", ["softmax", "identity", "gelu", "gelu_tanh", "silu"])
+def test_gdpa_backward_finite_differences(oracle, act):
+    rng = np.random.default_rng(21)
+    lens_kv, Nq, H, d = [6, 0, 3, 10], 3, 2, 5
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * 4, lens_kv, H, d)
+    d_o = rng.standard_normal(q.shape)
+    scale = 0.6
+    grads = oracle.gdpa_bwd(q, k, v, d_o, kv_off, scale, ACTS[act], max_q=Nq)
+    fwd = lambda a, b, c: oracle.gdpa_fwd(a, b, c, kv_off, scale, ACTS[act], max_q=Nq)[0]
+    _fd_check(fwd, grads, [q, k, v], d_o)
+    assert np.all(grads[0][Nq:2 * Nq] == 0.0)  # example without keys
+
+
+@pytest.mark.parametrize("window", [(2, 0), (1, 3), (-1, 0)])
+def test_swa_backward_finite_differences(oracle, window):
+    rng = np.random.default_rng(22)
+    lens = [7, 1, 5]
+    q, k, v, off, _ = rand_problem(rng, lens, lens, 2, 4)
+    d_o = rng.standard_normal(q.shape)
+    grads = oracle.swa_bwd(q, k, v, d_o, off, window[0], window[1], 0.5)
+    fwd = lambda a, b, c: oracle.swa_fwd(a, b, c, off, window[0], window[1], 0.5)[0]
+    _fd_check(fwd, grads, [q, k, v], d_o)
+
+
+# ---------- invariants ----------
+
+@pytest.mark.parametrize("act", ["softmax", "gelu"])
+def test_permutation_equivariance_and_invariance(oracle, act):
+    rng = np.random.default_rng(30)
+    lens_kv, Nq, H, d = [9, 4], 5, 2, 4
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * 2, lens_kv, H, d)
+    o, _ = oracle.gdpa_fwd(q, k, v, kv_off, 0.4, ACTS[act], max_q=Nq)
+    # permute the queries of each example: outputs permute the same way
+    perm_q = np.concatenate([b * Nq + rng.permutation(Nq) for b in range(2)])
+    o_p, _ = oracle.gdpa_fwd(q[perm_q], k, v, kv_off, 0.4, ACTS[act], max_q=Nq)
+    np.testing.assert_allclose(o_p, o[perm_q], rtol=1e-13, atol=1e-14)
+    # permute keys (with their values) inside each example: outputs unchanged
+    perm_k = np.concatenate([kv_off[b] + rng.permutation(lens_kv[b]) for b in range(2)])
+    o_k, _ = oracle.gdpa_fwd(q, k[perm_k], v[perm_k], kv_off, 0.4, ACTS[act], max_q=Nq)
+    np.testing.assert_allclose(o_k, o, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("act", ["softmax", "silu"])
+def test_examples_are_isolated(oracle, act):
+    """Changing another example's data, or rows past offsets[B], leaves example b bit-identical."""
+    rng = np.random.default_rng(31)
+    lens_kv, Nq, H, d = [5, 7, 3], 2, 2, 4
+    q, k, v, q_off, kv_off = rand_problem(rng, [Nq] * 3, lens_kv, H, d)
+    o, lse = oracle.gdpa_fwd(q, k, v, kv_off, 0.4, ACTS[act], max_q=Nq)
+    k2, v2, q2 = k.copy(), v.copy(), q.copy()
+    k2[kv_off[1]:kv_off[2]] = 99.0
+    v2[kv_off[1]:kv_off[2]] = -99.0
+    q2[Nq:2 * Nq] = 5.0
+    o2, lse2 = oracle.gdpa_fwd(q2, k2, v2, kv_off, 0.4, ACTS[act], max_q=Nq)
+    for b in (0, 2):
+        np.testing.assert_array_equal(o2[b * Nq:(b + 1) * Nq], o[b * Nq:(b + 1) * Nq])
+    # the same rows with trailing padding that no offset covers: first two examples only
+    o3, _ = oracle.gdpa_fwd(q[:2 * Nq], np.concatenate([k[:kv_off[2]]]), v[:kv_off[2]], kv_off[:3], 0.4, ACTS[act],
+                            max_q=Nq)
+    np.testing.assert_array_equal(o3, o[:2 * Nq])
+    # sliding window never crosses a sequence boundary
+    lens = [4, 6]
+    qs, ks, vs, off, _ = rand_problem(rng, lens, lens, 2, 4)
+    a, _ = oracle.swa_fwd(qs, ks, vs, off, 3, 3, 0.5)
+    ks2, vs2 = ks.copy(), vs.copy()
+    ks2[off[1]:] += 10.0
+    vs2[off[1]:] -= 10.0
+    b2, _ = oracle.swa_fwd(qs, ks2, vs2, off, 3, 3, 0.5)
+    np.testing.assert_array_equal(a[:off[1]], b2[:off[1]])
+
+
+def test_lse_consistency(oracle):
+    """exp(s_j - LSE) are the softmax weights: rebuilding O from LSE reproduces O."""
+    rng = np.random.default_rng(32)
+    q, k, v, q_off, kv_off = rand_problem(rng, [2], [6], 1, 3)
+    o, lse = oracle.gdpa_fwd(q, k, v, kv_off, 0.9, ACTS["softmax"], max_q=2)
+    s = 0.9 * q[:, 0] @ k[:, 0].T
+    p = np.exp(s - lse[0][:, None])
+    np.testing.assert_allclose(p.sum(axis=1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(p @ v[:, 0], o[:, 0], rtol=1e-12)
+
+
+def test_workload_recipes():
+    wl = W.make("cfg2", 0)
+    assert wl.total_kv == 144490 and wl.q.shape == (256 * 32, 4, 64) and wl.scale == 1 / 1024
+    assert np.array_equal(W.round_to_bf16(wl.k), wl.k)  # already representable
+    L4 = W.make_lengths("cfg4", 0)
+    assert L4.min() >= 32 and L4.max() <= 4096 and L4.size == 1024
+    x = np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -1.0 - 2 ** -8], dtype=np.float32)  # ties
+    np.testing.assert_array_equal(W.round_to_bf16(x), np.array([1.0, 1.0 + 2 ** -6, -1.0], dtype=np.float32))
+    np.testing.assert_array_equal(W.bf16_from_bits(W.bf16_bits(wl.v[:10])), wl.v[:10])
+    assert W.swa_pairs([5], 1, 0) == 9 and W.swa_pairs([3, 2], -1, -1) == 13
