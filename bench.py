@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the Kunlun attention hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic batch of the headline workload
+(BASELINE.json config "Large GDPA forward": B=1024, H=8, d=128, Nq=64, jagged log-normal
+history lengths):
+    kunlun_gdpa_fwd  (GELU score function, scale 1/tau)       Nq seed/context queries over the history
+    kunlun_gdpa_bwd  (dQ, dK, dV of the same call)
+    kunlun_swa_fwd   (window = previous 256 tokens)           self-attention over the same histories
+Inputs are resident in HBM before the timed region; the scheduler kernels are inside it.
+
+Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the whole step; `breakdown` gives each
+call alone (TFLOP/s, % of the bf16 MFMA peak, achieved GB/s, % of the HBM roofline);
+`roofline` describes the call that takes the longest; `cpu_baseline` is the CPU oracle timed on
+a bounded sample of the same batch.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
+HBM_PEAK = 8.0e12         # B/s
+WORKLOAD = "cfg4"
+WINDOW = (255, 0)
+ORACLE_SAMPLE_EXAMPLES = 48
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by the same counters on a copy kernel of known size; None until measured for a kernel
+# (see profiles/).  Keyed by breakdown name.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def device_normal(torch, shape, sigma, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    step = max(1, (1 << 27) // (shape[1] * shape[2]))
+    for s in range(0, shape[0], step):
+        e = min(shape[0], s + step)
+        out[s:e] = (torch.randn((e - s,) + tuple(shape[1:]), generator=g, device="cuda", dtype=torch.float32)
+                    * sigma).to(torch.bfloat16)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this library runs on ONE GPU (no collectives, no sharding); --gpus must be 1. "
+              "See DESIGN.md for how the path would shard by example.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_10016_amd import binding as kb
+    from paper_2602_10016_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    r = W.CONFIGS[WORKLOAD]
+    B, H, d, Nq, tau = r["B"], r["H"], r["d"], r["Nq"], r["tau"]
+    lengths = W.make_lengths(WORKLOAD, args.seed)
+    off_np = W.offsets_from_lengths(lengths)
+    T = int(off_np[-1])
+    max_kv = int(r["lengths"][4])
+    off = torch.from_numpy(off_np).cuda()
+    q = device_normal(torch, (B * Nq, H, d), r["sigma"], 11 + args.seed)
+    k = device_normal(torch, (T, H, d), r["sigma"], 12 + args.seed)
+    v = device_normal(torch, (T, H, d), r["sigma"], 13 + args.seed)
+    d_o = device_normal(torch, (B * Nq, H, d), 1.0, 14 + args.seed)
+    qs = device_normal(torch, (T, H, d), r["sigma"], 15 + args.seed)   # self-attention queries
+    scale_gdpa = 1.0 / tau
+    scale_swa = 1.0 / math.sqrt(d)
+    act = kb.ACT_GELU
+
+    o = torch.empty_like(q)
+    o_swa = torch.empty_like(qs)
+    ws_f = torch.empty(kb.workspace_bytes(kb.OP_GDPA_FWD, B, H, d, Nq, max_kv, B * Nq, T), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(max(256, kb.workspace_bytes(kb.OP_GDPA_BWD, B, H, d, Nq, max_kv, B * Nq, T)), dtype=torch.uint8, device="cuda")
+    ws_s = torch.empty(kb.workspace_bytes(kb.OP_SWA_FWD, B, H, d, max_kv, max_kv, T, T), dtype=torch.uint8, device="cuda")
+
+    def call_fwd():
+        kb.gdpa_fwd(q, k, v, off, scale_gdpa, act, max_q=Nq, max_kv=max_kv, out=o, want_lse=False, workspace=ws_f)
+
+    grads = {}
+
+    def call_bwd():
+        grads["g"] = kb.gdpa_bwd(q, k, v, d_o, off, scale_gdpa, act, max_q=Nq, max_kv=max_kv, workspace=ws_b)
+
+    def call_swa():
+        kb.swa_fwd(qs, k, v, off, WINDOW[0], WINDOW[1], scale_swa, max_len=max_kv, out=o_swa, want_lse=False, workspace=ws_s)
+
+    calls = [("gdpa_fwd", call_fwd), ("gdpa_bwd", call_bwd), ("swa_fwd", call_swa)]
+    pairs = W.swa_pairs(lengths, *WINDOW)
+    flops = {"gdpa_fwd": W.gdpa_flops(H, d, Nq, T), "gdpa_bwd": W.gdpa_flops(H, d, Nq, T, backward=True),
+             "swa_fwd": W.swa_flops(H, d, pairs)}
+    nbytes = {"gdpa_fwd": W.gdpa_bytes(H, d, B * Nq, T), "gdpa_bwd": W.gdpa_bytes(H, d, B * Nq, T, backward=True),
+              "swa_fwd": W.swa_bytes(H, d, T)}
+
+    for _ in range(args.warmup):
+        for _, fn in calls:
+            fn()
+    torch.cuda.synchronize()
+
+    # events on the stream the kernels are launched on (torch's current stream, which the binding uses)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        for i, (_, fn) in enumerate(calls):
+            fn()
+            ev[s][i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    call_ms = {name: sum(ev[s][i].elapsed_time(ev[s][i + 1]) for s in range(args.steps)) / args.steps
+               for i, (name, _) in enumerate(calls)}
+
+    total_flops = sum(flops.values())
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+    breakdown = {}
+    for name, _ in calls:
+        t = call_ms[name] * 1e-3
+        breakdown[name] = {"ms": round(call_ms[name], 4), "tflops": round(flops[name] / t / 1e12, 2),
+                           "pct_mfma_peak": round(100 * flops[name] / t / MFMA_BF16_PEAK, 2),
+                           "gbps": round(nbytes[name] / t / 1e9, 1),
+                           "pct_hbm_roofline": round(100 * nbytes[name] / t / HBM_PEAK, 2),
+                           "gflop": round(flops[name] / 1e9, 2), "mbytes": round(nbytes[name] / 1e6, 1)}
+    dom = max(call_ms, key=call_ms.get)
+    achieved = nbytes[dom] / (call_ms[dom] * 1e-3) / 1e9
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": round(achieved / (HBM_PEAK / 1e9), 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(ORACLE_SAMPLE_EXAMPLES, B)
+        kv_n = int(off_np[n])
+        host = lambda t: t.float().cpu().numpy().astype(np.float64)
+        hq, hk, hv, hdo, hqs = host(q[:n * Nq]), host(k[:kv_n]), host(v[:kv_n]), host(d_o[:n * Nq]), host(qs[:kv_n])
+        sub_off = off_np[:n + 1]
+        t1 = time.perf_counter()
+        oracle.gdpa_fwd(hq, hk, hv, sub_off, scale_gdpa, act, max_q=Nq)
+        oracle.gdpa_bwd(hq, hk, hv, hdo, sub_off, scale_gdpa, act, max_q=Nq)
+        oracle.swa_fwd(hqs, hk, hv, sub_off, WINDOW[0], WINDOW[1], scale_swa)
+        cpu_s = time.perf_counter() - t1
+        sub_flops = (W.gdpa_flops(H, d, Nq, kv_n) + W.gdpa_flops(H, d, Nq, kv_n, backward=True)
+                     + W.swa_flops(H, d, W.swa_pairs(lengths[:n], *WINDOW)))
+        cpu_baseline = {"value": round(sub_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "seconds": round(cpu_s, 2),
+                        "sample": f"first {n} of {B} examples of the same batch ({kv_n} history tokens), same three "
+                                  f"calls, fp64"}
+
+    out = {
+        "metric": "GDPA fwd/bwd TFLOP/s + % of MI355X bf16 MFMA peak, jagged B=1024",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_mfma_peak": round(100 * value * 1e12 / MFMA_BF16_PEAK, 2),
+        "config": {"workload": f"{WORKLOAD}: B={B} H={H} d={d} Nq={Nq}, history lengths lognormal(median 800, "
+                               f"sigma 1) clipped [32,4096], T={T} tokens; step = gdpa_fwd(gelu, 1/tau) + gdpa_bwd + "
+                               f"swa_fwd(window 256 causal) on the same batch", "seed": args.seed,
+                   "step_gflop": round(total_flops / 1e9, 1)},
+        "breakdown": breakdown, "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,145 @@
+/*
+ * kunlun.h - C ABI of the Kunlun attention library for AMD Instinct MI355X (gfx950).
+ *
+ * Three operators of the Kunlun architecture (arXiv 2602.10016) as fused, jagged-aware
+ * GPU kernels:
+ *
+ *   kunlun_gdpa_fwd  Generalized Dot-Product Attention, Eq. (GDPA) of Sec. "Multi-Head
+ *                    PFFN with Generalized Dot-Product Attention" and the per-head line of
+ *                    Alg. "Generalized Dot-Product Attention":
+ *                        O_h = Act_h(Q_h K_h^T * scale) V_h ,  scale = 1/tau,
+ *                    with an element-wise score function per head and no normaliser; and,
+ *                    with KUNLUN_ACT_SOFTMAX, the multi-head attention of Eq. (PMA) and of
+ *                    Eq. (seed-level attention) in Sec. "Hierarchical Seed Pooling":
+ *                        O_h = softmax(Q_h K_h^T * scale) V_h .
+ *   kunlun_gdpa_bwd  Gradient of <O, dO> with respect to Q, K, V of the above (the fused
+ *                    backward pass that Sec. "Efficient Attention-Style Implementation" and
+ *                    App. "GDPA and Fused PFFN Kernel" describe: scores are recomputed
+ *                    tile by tile, no score-sized tensor is stored).
+ *   kunlun_swa_fwd   Sliding-window self-attention, Eq. (sliding window) of Sec. "Sliding
+ *                    Window Attention": query t attends to keys [t-left, t+right] of its
+ *                    own sequence under softmax.
+ *
+ * Jagged layout.  A batch holds B examples.  Tensors are packed "tokens, heads, channels":
+ *   Q  [total_q,  H, d]      O, dO, dQ like Q
+ *   K,V[total_kv, H, d]      dK, dV like K
+ *   LSE[H, total_q] float    (softmax mode only)
+ * row-major and contiguous.  Example b owns key rows kv_offsets[b] .. kv_offsets[b+1]-1 and
+ * query rows q_offsets[b] .. q_offsets[b+1]-1; with q_offsets == NULL every example owns
+ * exactly max_q query rows (b*max_q ..).  Keys of other examples are never read for example
+ * b and contribute exactly nothing.  An example without keys gets zero output rows (and
+ * LSE = -inf, zero gradients).
+ *
+ * Memory.  q, k, v, o, lse, d_o, dq, dk, dv, *_offsets and workspace are DEVICE pointers;
+ * head_act is a HOST pointer.  The caller owns every buffer.  The library allocates
+ * nothing, keeps no state between calls and never synchronises: kernels are enqueued on
+ * `stream` (a hipStream_t, NULL = default stream) and the call returns at once.  Tensor
+ * pointers must be 16-byte aligned.  `workspace` must hold at least
+ * kunlun_workspace_bytes(...) bytes, 256-byte aligned; its contents are scratch (work
+ * lists, counters, partial results) and calls that share a workspace must be ordered on
+ * one stream.  Offsets are trusted: offsets[0] = 0, non-decreasing, offsets[B] = total.
+ *
+ * Data types.  KUNLUN_BF16: bf16 storage, fp32 accumulation, outputs rounded to nearest
+ * even; the two contractions run on the matrix cores when d is 64 or 128.  KUNLUN_FP32:
+ * fp32 storage and arithmetic throughout.  Supported d: multiples of 8 up to 256.
+ *
+ * Errors.  Every entry point validates its arguments on the host before anything is
+ * enqueued and returns a kunlun_status (0 = OK, negative = error); nothing is launched on
+ * error.  No exceptions, no abort.
+ */
+#ifndef KUNLUN_H_
+#define KUNLUN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KUNLUN_OK = 0,
+    KUNLUN_ERR_NULL = -1,        /* a required pointer is NULL */
+    KUNLUN_ERR_SHAPE = -2,       /* negative or inconsistent sizes */
+    KUNLUN_ERR_UNSUPPORTED = -3, /* unknown dtype / activation, unsupported d or H */
+    KUNLUN_ERR_ALIGN = -4,       /* a pointer is not aligned as required */
+    KUNLUN_ERR_WORKSPACE = -5,   /* workspace missing or too small */
+    KUNLUN_ERR_LAUNCH = -6       /* the HIP runtime refused a launch */
+} kunlun_status;
+
+typedef enum { KUNLUN_BF16 = 0, KUNLUN_FP32 = 1 } kunlun_dtype;
+
+/* Score functions.  gelu(x) = x * Phi(x) (erf form); gelu_tanh is the tanh approximation
+ * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))); silu(x) = x / (1 + exp(-x)). */
+typedef enum {
+    KUNLUN_ACT_SOFTMAX = 0,
+    KUNLUN_ACT_IDENTITY = 1,
+    KUNLUN_ACT_RELU = 2,
+    KUNLUN_ACT_GELU = 3,
+    KUNLUN_ACT_GELU_TANH = 4,
+    KUNLUN_ACT_SILU = 5
+} kunlun_act;
+
+typedef enum { KUNLUN_OP_GDPA_FWD = 0, KUNLUN_OP_GDPA_BWD = 1, KUNLUN_OP_SWA_FWD = 2 } kunlun_op;
+
+#define KUNLUN_MAX_HEADS 64
+
+/*
+ * Forward GDPA / multi-head attention over jagged keys (Eq. (GDPA); Eq. (PMA), Eq.
+ * (seed-level attention) with KUNLUN_ACT_SOFTMAX).
+ *   q, k, v      in,  device, `dtype` elements, layouts above
+ *   o            out, device, like q; every row of every example is written
+ *   lse          out, device, float [H, total_q], may be NULL; written for softmax heads only
+ *   q_offsets    in,  device int32 [B+1] or NULL (dense queries: max_q rows per example)
+ *   kv_offsets   in,  device int32 [B+1]
+ *   max_q,max_kv upper bounds on the per-example query / key counts (sizing only; the true
+ *                counts come from the offsets); total_q, total_kv: row counts of q and k
+ *   scale        multiplies the dot products (1/tau for GDPA, 1/sqrt(d) for softmax)
+ *   act          kunlun_act used by every head unless head_act is given
+ *   head_act     in, HOST int32 [H] or NULL: per-head kunlun_act ("Act_h")
+ * B == 0 or total_q == 0 is legal and does nothing.
+ */
+int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
+                    const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                    int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of kunlun_gdpa_fwd: dq, dk, dv (out, device, shaped like q, k, v, fully
+ * overwritten) from q, k, v and the upstream gradient d_o (in, device, like q).
+ * With p the weight of a (query, key) pair and dp = <dO_row, V_row>:
+ *     dV += p dO;   activation heads: ds = dp Act'(s) scale;
+ *     softmax heads: ds = p (dp - rowsum(dO * O)) scale;   dQ += ds K;   dK += ds Q.
+ * o and lse (in, device) are the forward outputs; they are read for softmax heads only and
+ * may be NULL when no head uses softmax.  Other arguments as in kunlun_gdpa_fwd.
+ */
+int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                    void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H,
+                    int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, float scale, int act,
+                    const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sliding-window softmax self-attention over jagged sequences (Eq. (sliding window)).
+ * q, k, v, o share `offsets` (device int32 [B+1]) and have `total` rows.  The query at
+ * position t of a sequence of length L sees keys max(0, t-window_left) ..
+ * min(L-1, t+window_right); a negative bound means unbounded on that side, so (-1, -1) is
+ * full attention and (-1, 0) causal attention.  The equation's symmetric window of size w is
+ * (w, w); "the previous W tokens including itself" is (W-1, 0).  lse: float [H, total] or NULL.
+ */
+int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* offsets, int B,
+                   int H, int d, int max_len, int64_t total, int window_left, int window_right, float scale,
+                   int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace that a call of `op` (kunlun_op) with these sizes needs.  Returns 0 for
+ * an unknown op or negative sizes.  For KUNLUN_OP_SWA_FWD pass max_len as max_q and max_kv
+ * and total as total_q and total_kv. */
+size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                              int64_t total_kv);
+
+/* Static, human-readable text for a kunlun_status. */
+const char* kunlun_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KUNLUN_H_ */

@@ -1,0 +1,192 @@
+// C ABI of the library (see include/kunlun.h): argument validation on the host, then the
+// scheduler kernel and the attention kernels are enqueued on the caller's stream.  Nothing
+// here allocates, synchronises or keeps state.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+using namespace kunlun;
+
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_common(int B, int H, int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, float scale,
+                 int dtype) {
+    if (B < 0 || H <= 0 || d <= 0 || max_q < 0 || max_kv < 0 || total_q < 0 || total_kv < 0) return KUNLUN_ERR_SHAPE;
+    if (total_q >= (int64_t)1 << 31 || total_kv >= (int64_t)1 << 31) return KUNLUN_ERR_SHAPE;  // int32 offsets
+    if (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32) return KUNLUN_ERR_UNSUPPORTED;
+    if (H > KUNLUN_MAX_HEADS || d > 256 || d % 8 != 0) return KUNLUN_ERR_UNSUPPORTED;
+    if (!std::isfinite(scale)) return KUNLUN_ERR_UNSUPPORTED;
+    if (total_q * (int64_t)H >= (int64_t)1 << 31 || total_kv * (int64_t)H >= (int64_t)1 << 31)
+        return KUNLUN_ERR_UNSUPPORTED;  // one workgroup per (row, head) must fit a 1-D grid
+    return KUNLUN_OK;
+}
+
+int fill_acts(AttnParams& p, int H, int act, const int32_t* head_act, bool& any_softmax) {
+    any_softmax = false;
+    for (int h = 0; h < H; ++h) {
+        const int a = head_act ? head_act[h] : act;
+        if (a < KUNLUN_ACT_SOFTMAX || a > KUNLUN_ACT_SILU) return KUNLUN_ERR_UNSUPPORTED;
+        p.head_act[h] = (uint8_t)a;
+        any_softmax |= a == KUNLUN_ACT_SOFTMAX;
+    }
+    return KUNLUN_OK;
+}
+
+size_t order_bytes(int B) { return align_up((size_t)(B + 1) * sizeof(int32_t), 256); }
+
+}  // namespace
+
+extern "C" {
+
+size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                              int64_t total_kv) {
+    if (B < 0 || H <= 0 || d <= 0 || max_q < 0 || max_kv < 0 || total_q < 0 || total_kv < 0) return 0;
+    switch (op) {
+    case KUNLUN_OP_GDPA_FWD:
+    case KUNLUN_OP_SWA_FWD:
+        return WS_HEADER_BYTES + order_bytes(B);
+    case KUNLUN_OP_GDPA_BWD:
+        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_workspace_tail(B, H, d, max_q, total_q);
+    default:
+        return 0;
+    }
+}
+
+const char* kunlun_strerror(int status) {
+    switch (status) {
+    case KUNLUN_OK: return "ok";
+    case KUNLUN_ERR_NULL: return "a required pointer is NULL";
+    case KUNLUN_ERR_SHAPE: return "negative or inconsistent sizes";
+    case KUNLUN_ERR_UNSUPPORTED: return "unsupported dtype, activation, head count or head dimension";
+    case KUNLUN_ERR_ALIGN: return "a pointer is not aligned as required";
+    case KUNLUN_ERR_WORKSPACE: return "workspace missing or too small";
+    case KUNLUN_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+    }
+}
+
+int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
+                    const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                    int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    int rc = check_common(B, H, d, max_q, max_kv, total_q, total_kv, scale, dtype);
+    if (rc != KUNLUN_OK) return rc;
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    bool any_softmax;
+    rc = fill_acts(p, H, act, head_act, any_softmax);
+    if (rc != KUNLUN_OK) return rc;
+    if (!q_offsets && (int64_t)B * max_q != total_q) return KUNLUN_ERR_SHAPE;
+    if (B == 0 || total_q == 0) return KUNLUN_OK;
+    if (!q || !o || !kv_offsets) return KUNLUN_ERR_NULL;
+    if (total_kv > 0 && (!k || !v)) return KUNLUN_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lse, 4) ||
+        !aligned(q_offsets, 4) || !aligned(kv_offsets, 4))
+        return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_GDPA_FWD, B, H, d, max_q, max_kv, total_q, total_kv))
+        return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+
+    p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+    p.q_off = q_offsets; p.kv_off = kv_offsets;
+    p.B = B; p.H = H; p.d = d; p.max_q = max_q; p.max_kv = max_kv;
+    p.total_q = total_q; p.total_kv = total_kv; p.scale = scale;
+    p.windowed = 0; p.left = -1; p.right = -1;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_fwd_supported(p, dtype)) {
+        int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
+        p.order = order;
+        e = launch_schedule(kv_offsets, B, max_kv, order, s);
+        if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        e = launch_mfma_fwd(p, s);
+    } else {
+        e = launch_scalar_fwd(p, dtype, s);
+    }
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
+int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                    void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H,
+                    int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, float scale, int act,
+                    const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_common(B, H, d, max_q, max_kv, total_q, total_kv, scale, dtype);
+    if (rc != KUNLUN_OK) return rc;
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    bool any_softmax;
+    rc = fill_acts(p, H, act, head_act, any_softmax);
+    if (rc != KUNLUN_OK) return rc;
+    if (!q_offsets && (int64_t)B * max_q != total_q) return KUNLUN_ERR_SHAPE;
+    if (B == 0 || (total_q == 0 && total_kv == 0)) return KUNLUN_OK;
+    if (!kv_offsets) return KUNLUN_ERR_NULL;
+    if (total_q > 0 && (!q || !d_o || !dq)) return KUNLUN_ERR_NULL;
+    if (total_kv > 0 && (!k || !v || !dk || !dv)) return KUNLUN_ERR_NULL;
+    if (any_softmax && total_q > 0 && (!o || !lse)) return KUNLUN_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(d_o, 16) ||
+        !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lse, 4) || !aligned(q_offsets, 4) ||
+        !aligned(kv_offsets, 4))
+        return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_GDPA_BWD, B, H, d, max_q, max_kv, total_q, total_kv))
+        return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+
+    p.q = q; p.k = k; p.v = v; p.o = const_cast<void*>(o); p.lse = const_cast<float*>(lse); p.d_o = d_o;
+    p.dq = dq; p.dk = dk; p.dv = dv;
+    p.q_off = q_offsets; p.kv_off = kv_offsets;
+    p.B = B; p.H = H; p.d = d; p.max_q = max_q; p.max_kv = max_kv;
+    p.total_q = total_q; p.total_kv = total_kv; p.scale = scale;
+    p.windowed = 0; p.left = -1; p.right = -1;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_bwd_supported(p, dtype)) {
+        int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
+        p.order = order;
+        e = launch_schedule(kv_offsets, B, max_kv, order, s);
+        if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        e = launch_mfma_bwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
+    } else {
+        e = launch_scalar_bwd(p, dtype, s);
+    }
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
+int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* offsets, int B,
+                   int H, int d, int max_len, int64_t total, int window_left, int window_right, float scale,
+                   int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_common(B, H, d, max_len, max_len, total, total, scale, dtype);
+    if (rc != KUNLUN_OK) return rc;
+    if (B == 0 || total == 0) return KUNLUN_OK;
+    if (!q || !k || !v || !o || !offsets) return KUNLUN_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(lse, 4) ||
+        !aligned(offsets, 4))
+        return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_SWA_FWD, B, H, d, max_len, max_len, total, total))
+        return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    for (int h = 0; h < H; ++h) p.head_act[h] = KUNLUN_ACT_SOFTMAX;
+    p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
+    p.q_off = offsets; p.kv_off = offsets;
+    p.B = B; p.H = H; p.d = d; p.max_q = max_len; p.max_kv = max_len;
+    p.total_q = total; p.total_kv = total; p.scale = scale;
+    p.windowed = 1;
+    p.left = window_left < 0 ? -1 : window_left;
+    p.right = window_right < 0 ? -1 : window_right;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_fwd_supported(p, dtype)) {
+        p.order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);  // holds the query-tile prefix sums
+        e = launch_mfma_fwd(p, s);
+    } else {
+        e = launch_scalar_fwd(p, dtype, s);
+    }
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,326 @@
+// bf16 matrix-core forward kernels for gfx950: GDPA (Eq. (GDPA)), softmax attention of a few
+// seed / context queries over a jagged history (Eq. (PMA), Eq. (seed-level attention)) and
+// sliding-window self-attention (Eq. (sliding window)).
+//
+// One wavefront = one work item = (example, head, tile of up to 32*NQB queries); a workgroup
+// is a single wavefront, so there is no barrier anywhere: every wave streams the K/V rows of
+// its own item HBM -> registers -> its private LDS tile -> MFMA operands, with the loads of
+// tile t+1 in flight while tile t is computed.  These operators do Nq flops per byte of K/V
+// (each key/value byte is used only by the queries of its own example and head), far below
+// the matrix-core ridge, so the design goal is bytes in flight, not MFMA occupancy.
+//
+// Per 32-key tile:  S^T = K Q^T (MFMA, Q^T fragments resident in registers)
+//                   P^T = score function of S^T * scale in registers (masked past the end of
+//                         the history / outside the window), packed to bf16
+//                   O^T += V^T P^T (MFMA, V^T via transposing LDS reads)
+// Softmax keeps a running maximum and sum per query (one query per lane column) and
+// rescales O^T when the maximum grows; the activation path has no such stage.
+#include "mfma_tile.h"
+
+namespace kunlun {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int D, int NQB, int ACT, bool WINDOWED>
+__device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq,
+                                              int64_t t0, int64_t k0, int n_kv) {
+    using L = TileLayout<D>;
+    constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
+    constexpr int KC = D / 16;  // contraction steps of S^T = K Q^T
+    constexpr int DB = D / 32;  // 32-channel blocks of O^T
+    const int lane = threadIdx.x;
+    const int r = lane & 31, g = lane >> 5;
+    const int64_t hd = (int64_t)p.H * D;
+    const bf16_t* Q = (const bf16_t*)p.q;
+    const bf16_t* K = (const bf16_t*)p.k + (k0 * p.H + h) * D;
+    const bf16_t* V = (const bf16_t*)p.v + (k0 * p.H + h) * D;
+    char* ldsK = lds;
+    char* ldsV = lds + L::TILE_BYTES;
+
+    // key tiles this item touches
+    int kt_begin = 0, kt_end = (n_kv + KT - 1) / KT;
+    if (WINDOWED && n_kv > 0) {
+        int64_t key_lo = 0, key_hi = n_kv - 1;
+        if (p.left >= 0 && t0 - p.left > key_lo) key_lo = t0 - p.left;
+        if (p.right >= 0 && t0 + nq - 1 + p.right < key_hi) key_hi = t0 + nq - 1 + p.right;
+        kt_begin = (int)(key_lo / KT);
+        kt_end = (int)(key_hi / KT) + 1;
+    }
+
+    // Q^T fragments (B operand): column = query 32*qb + r, contraction = channels 16*kc + 8g..
+    bf16x8 qf[NQB][KC];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        int qi = 32 * qb + r;
+        qi = qi < nq ? qi : nq - 1;
+        const bf16_t* qrow = Q + (q_row0 + qi) * hd + (int64_t)h * D + 8 * g;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *(const bf16x8*)(qrow + 16 * kc);
+    }
+
+    f32x16 oacc[DB][NQB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[db][qb][v] = 0.f;
+    float m_run[NQB], l_run[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    const float sc = SOFTMAX ? p.scale * LOG2E : p.scale;
+
+    u32x4 kst[L::LOADS], vst[L::LOADS];
+    if (kt_begin < kt_end) {
+        const int rows = n_kv - kt_begin * KT;
+        load_tile_regs<D>(kst, K + (int64_t)kt_begin * KT * hd, hd, rows, lane);
+        load_tile_regs<D>(vst, V + (int64_t)kt_begin * KT * hd, hd, rows, lane);
+    }
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        store_k_tile<D>(ldsK, kst, lane);
+        store_v_tile<D>(ldsV, vst, lane);
+        if (kt + 1 < kt_end) {
+            const int rows = n_kv - (kt + 1) * KT;
+            load_tile_regs<D>(kst, K + (int64_t)(kt + 1) * KT * hd, hd, rows, lane);
+            load_tile_regs<D>(vst, V + (int64_t)(kt + 1) * KT * hd, hd, rows, lane);
+        }
+        // ---- S^T = K Q^T
+        f32x16 sacc[NQB];
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 a = read_k_frag<D>(ldsK, kc, r, g);
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) sacc[qb] = mfma32(a, qf[qb][kc], sacc[qb]);
+        }
+        // ---- score function, masking, packing
+        const int key_base = kt * KT;
+        bool need_mask = key_base + KT > n_kv;
+        if (WINDOWED) {
+            // interior tile: every (valid query, key) pair of the tile is inside the window
+            const int64_t tq_lo = t0, tq_hi = t0 + nq - 1;
+            if (p.left >= 0 && key_base < tq_hi - p.left) need_mask = true;
+            if (p.right >= 0 && key_base + KT - 1 > tq_lo + p.right) need_mask = true;
+        }
+        bf16x8 pf[NQB][2];
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+            float pv[16];  // scaled scores, then weights
+            if (need_mask) {
+                const int64_t tq = t0 + 32 * qb + r;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int64_t key = key_base + c_row(v, g);
+                    bool ok = key < n_kv;
+                    if (WINDOWED) {
+                        if (p.left >= 0 && key < tq - p.left) ok = false;
+                        if (p.right >= 0 && key > tq + p.right) ok = false;
+                    }
+                    const float s = sacc[qb][v] * sc;
+                    if (SOFTMAX) pv[v] = ok ? s : -INFINITY;
+                    else pv[v] = ok ? act_fast<ACT>(s) : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float s = sacc[qb][v] * sc;
+                    pv[v] = SOFTMAX ? s : act_fast<ACT>(s);
+                }
+            }
+            if (SOFTMAX) {
+                // scores are in log2 units (scale * log2 e folded into sc)
+                float mx = pv[0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, pv[v]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // the other lane half holds the other 16 keys
+                const float m_new = fmaxf(m_run[qb], mx);
+                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+                const float corr = fast_exp2(m_run[qb] - m_safe);
+                float sum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    pv[v] = fast_exp2(pv[v] - m_safe);
+                    sum += pv[v];
+                }
+                l_run[qb] = l_run[qb] * corr + sum;
+                m_run[qb] = m_new;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= corr;
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[qb][c][e] = (bf16_t)pv[8 * c + e];
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const bf16x8 a = read_vt_frag<D>(ldsV, db, c, lane);
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb) oacc[db][qb] = mfma32(a, pf[qb][c], oacc[db][qb]);
+            }
+        }
+    }
+
+    // ---- epilogue: lane holds query 32*qb + r, channels 32*db + 8*(v/4) + 4g + (v%4)
+    bf16_t* O = (bf16_t*)p.o;
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const int qi = 32 * qb + r;
+        float inv = 1.f;
+        if (SOFTMAX) {
+            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+            inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            if (p.lse && g == 0 && qi < nq)
+                p.lse[(int64_t)h * p.total_q + q_row0 + qi] =
+                    l_tot > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
+        }
+        if (qi < nq) {
+            bf16_t* orow = O + (q_row0 + qi) * hd + (int64_t)h * D + 4 * g;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    bf16x4 out;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) out[e] = (bf16_t)(oacc[db][qb][4 * vg + e] * inv);
+                    *(bf16x4*)(orow + 32 * db + 8 * vg) = out;
+                }
+        }
+    }
+}
+
+template <int D, int NQB, bool WINDOWED>
+__device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds, int act, int h, int64_t q_row0,
+                                                  int nq, int64_t t0, int64_t k0, int n_kv) {
+    if (WINDOWED) {
+        attn_fwd_item<D, NQB, KUNLUN_ACT_SOFTMAX, true>(p, lds, h, q_row0, nq, t0, k0, n_kv);
+    } else {
+        switch (act) {
+        case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, KUNLUN_ACT_SOFTMAX, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, KUNLUN_ACT_IDENTITY, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, KUNLUN_ACT_RELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, KUNLUN_ACT_GELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, KUNLUN_ACT_GELU_TANH, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        default: attn_fwd_item<D, NQB, KUNLUN_ACT_SILU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        }
+    }
+}
+
+// GDPA / cross attention: grid = B * n_qtiles * H work items, examples in scheduler order
+// (longest history first).  item -> head fastest, then query tile, then example.
+template <int D, int NQB>
+__global__ __launch_bounds__(64) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TileLayout<D>::TILE_BYTES];
+    const int64_t item = blockIdx.x;
+    const int h = (int)(item % p.H);
+    const int64_t e = item / p.H;
+    const int qt = (int)(e % n_qtiles);
+    const int b = p.order[e / n_qtiles];
+    const int64_t qb0 = q_begin(p, b);
+    const int64_t nq_all = q_end(p, b) - qb0;
+    const int64_t q_first = (int64_t)qt * 32 * NQB;
+    if (q_first >= nq_all) return;
+    const int nq = (int)((nq_all - q_first) < 32 * NQB ? (nq_all - q_first) : 32 * NQB);
+    const int64_t k0 = p.kv_off[b];
+    const int n_kv = p.kv_off[b + 1] - (int)k0;
+    attn_fwd_dispatch<D, NQB, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
+}
+
+// Sliding-window self-attention: grid = H * (query tiles of all sequences), cut into 8
+// contiguous ranges, one per XCD (workgroup i runs on XCD i % 8), so that the query tiles of
+// one (sequence, head) - which share most of their keys - meet in the same L2.
+// tile_start[b] = number of query tiles before sequence b (written by the prefix kernel).
+template <int D, int NQB>
+__global__ __launch_bounds__(64) void swa_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
+    __shared__ __attribute__((aligned(1024))) char lds[2 * TileLayout<D>::TILE_BYTES];
+    const int64_t n_items = (int64_t)tile_start[p.B] * p.H;
+    const int64_t per_xcd = (n_items + 7) / 8;
+    const int xcd = blockIdx.x & 7;
+    const int64_t slot = blockIdx.x >> 3;
+    if (slot >= per_xcd) return;
+    const int64_t item = xcd * per_xcd + slot;
+    if (item >= n_items) return;
+    // items ordered by sequence, then head, then query tile
+    int lo = 0, hi = p.B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)tile_start[mid] * p.H <= item) lo = mid; else hi = mid - 1;
+    }
+    const int b = lo;
+    const int nt = tile_start[b + 1] - tile_start[b];
+    const int64_t rem = item - (int64_t)tile_start[b] * p.H;
+    const int h = (int)(rem / nt);
+    const int qt = (int)(rem % nt);
+    const int64_t k0 = p.kv_off[b];
+    const int n_kv = p.kv_off[b + 1] - (int)k0;
+    const int64_t q_first = (int64_t)qt * 32 * NQB;
+    const int nq = (int)((n_kv - q_first) < 32 * NQB ? (n_kv - q_first) : 32 * NQB);
+    attn_fwd_dispatch<D, NQB, true>(p, lds, KUNLUN_ACT_SOFTMAX, h, k0 + q_first, nq, q_first, k0, n_kv);
+}
+
+// Exclusive prefix sum of ceil(len_b / tile) over the sequences, single workgroup.
+__global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int B, int tile,
+                                                           int32_t* __restrict__ tile_start) {
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int per = (B + 1023) / 1024;
+    const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
+    int sum = 0;
+    for (int b = b0; b < b1; ++b) sum += (off[b + 1] - off[b] + tile - 1) / tile;
+    part[tid] = sum;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int v = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int run = part[tid] - sum;
+    for (int b = b0; b < b1; ++b) {
+        tile_start[b] = run;
+        run += (off[b + 1] - off[b] + tile - 1) / tile;
+    }
+    if (tid == 1023) tile_start[B] = part[1023];
+}
+
+bool mfma_fwd_supported(const AttnParams& p, int dtype) {
+    return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128);
+}
+
+hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
+    if (p.windowed) {
+        // self-attention: 64-query tiles; an upper bound of the tile count sizes the grid
+        const int64_t max_tiles = p.total_q / 64 + p.B;
+        const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
+        const unsigned grid = (unsigned)(per_xcd * 8);
+        int32_t* tile_start = const_cast<int32_t*>(p.order);
+        hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.kv_off, p.B, 64, tile_start);
+        if (p.d == 128)
+            hipLaunchKernelGGL((swa_fwd_mfma_kernel<128, 2>), dim3(grid), dim3(64), 0, stream, p, tile_start);
+        else
+            hipLaunchKernelGGL((swa_fwd_mfma_kernel<64, 2>), dim3(grid), dim3(64), 0, stream, p, tile_start);
+        return hipGetLastError();
+    }
+    const bool one_block = p.max_q <= 32;
+    const int qtile = one_block ? 32 : 64;
+    const int n_qtiles = (p.max_q + qtile - 1) / qtile;
+    const unsigned grid = (unsigned)((int64_t)p.B * n_qtiles * p.H);
+    if (p.d == 128) {
+        if (one_block) hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<128, 1>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
+        else hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<128, 2>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
+    } else {
+        if (one_block) hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<64, 1>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
+        else hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<64, 2>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace kunlun

@@ -1,0 +1,140 @@
+// Shared declarations of the Kunlun attention kernels (device side) and their host launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kunlun.h"
+
+namespace kunlun {
+
+typedef __bf16 bf16_t;
+
+// Everything a kernel needs, passed by value as the single kernel argument.
+struct AttnParams {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;           // forward output, or the forward result read by the softmax backward
+    float* lse;        // [H, total_q]; may be null in the forward pass
+    const void* d_o;   // backward only
+    void* dq;
+    void* dk;
+    void* dv;
+    const int32_t* q_off;   // null: dense queries, max_q rows per example
+    const int32_t* kv_off;
+    const int32_t* order;   // examples, longest history first (written by the scheduler kernel)
+    int B, H, d, max_q, max_kv;
+    int64_t total_q, total_kv;
+    float scale;
+    int windowed, left, right;  // sliding window (self-attention); left/right < 0: unbounded
+    uint8_t head_act[KUNLUN_MAX_HEADS];
+};
+
+// Workspace layout (bytes from the start of the caller's workspace).
+constexpr size_t WS_HEADER_BYTES = 256;  // counters
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
+hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
+hipError_t launch_scalar_fwd(const AttnParams& p, int dtype, hipStream_t stream);
+hipError_t launch_scalar_bwd(const AttnParams& p, int dtype, hipStream_t stream);
+bool mfma_fwd_supported(const AttnParams& p, int dtype);
+hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream);
+bool mfma_bwd_supported(const AttnParams& p, int dtype);
+hipError_t launch_mfma_bwd(const AttnParams& p, void* workspace_tail, hipStream_t stream);
+size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
+
+#ifdef __HIPCC__
+// ---- device helpers ----
+
+__device__ __forceinline__ int64_t q_begin(const AttnParams& p, int b) {
+    return p.q_off ? (int64_t)p.q_off[b] : (int64_t)b * p.max_q;
+}
+__device__ __forceinline__ int64_t q_end(const AttnParams& p, int b) {
+    return p.q_off ? (int64_t)p.q_off[b + 1] : (int64_t)(b + 1) * p.max_q;
+}
+
+// Largest b in [0, B) with off[b] <= row (rows of empty examples are skipped naturally).
+__device__ __forceinline__ int find_example(const int32_t* off, int B, int64_t row) {
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if ((int64_t)off[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Exact score functions (fp32 path): definitions as in include/kunlun.h.
+template <int ACT>
+__device__ __forceinline__ float act_exact(float x) {
+    if constexpr (ACT == KUNLUN_ACT_IDENTITY) return x;
+    if constexpr (ACT == KUNLUN_ACT_RELU) return x > 0.f ? x : 0.f;
+    if constexpr (ACT == KUNLUN_ACT_GELU) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));
+    if constexpr (ACT == KUNLUN_ACT_GELU_TANH) {
+        float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+        return 0.5f * x * (1.f + tanhf(u));
+    }
+    if constexpr (ACT == KUNLUN_ACT_SILU) return x / (1.f + expf(-x));
+    return 0.f;
+}
+
+template <int ACT>
+__device__ __forceinline__ float act_deriv_exact(float x) {
+    if constexpr (ACT == KUNLUN_ACT_IDENTITY) return 1.f;
+    if constexpr (ACT == KUNLUN_ACT_RELU) return x > 0.f ? 1.f : 0.f;
+    if constexpr (ACT == KUNLUN_ACT_GELU) {
+        float cdf = 0.5f * (1.f + erff(x * 0.70710678118654752f));
+        float pdf = 0.39894228040143268f * expf(-0.5f * x * x);
+        return cdf + x * pdf;
+    }
+    if constexpr (ACT == KUNLUN_ACT_GELU_TANH) {
+        float u = 0.79788456080286536f * (x + 0.044715f * x * x * x);
+        float t = tanhf(u);
+        float du = 0.79788456080286536f * (1.f + 3.f * 0.044715f * x * x);
+        return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * du;
+    }
+    if constexpr (ACT == KUNLUN_ACT_SILU) {
+        float s = 1.f / (1.f + expf(-x));
+        return s + x * s * (1.f - s);
+    }
+    return 0.f;
+}
+
+__device__ __forceinline__ float act_exact_rt(int act, float x) {
+    switch (act) {
+    case KUNLUN_ACT_IDENTITY: return act_exact<KUNLUN_ACT_IDENTITY>(x);
+    case KUNLUN_ACT_RELU: return act_exact<KUNLUN_ACT_RELU>(x);
+    case KUNLUN_ACT_GELU: return act_exact<KUNLUN_ACT_GELU>(x);
+    case KUNLUN_ACT_GELU_TANH: return act_exact<KUNLUN_ACT_GELU_TANH>(x);
+    default: return act_exact<KUNLUN_ACT_SILU>(x);
+    }
+}
+__device__ __forceinline__ float act_deriv_exact_rt(int act, float x) {
+    switch (act) {
+    case KUNLUN_ACT_IDENTITY: return act_deriv_exact<KUNLUN_ACT_IDENTITY>(x);
+    case KUNLUN_ACT_RELU: return act_deriv_exact<KUNLUN_ACT_RELU>(x);
+    case KUNLUN_ACT_GELU: return act_deriv_exact<KUNLUN_ACT_GELU>(x);
+    case KUNLUN_ACT_GELU_TANH: return act_deriv_exact<KUNLUN_ACT_GELU_TANH>(x);
+    default: return act_deriv_exact<KUNLUN_ACT_SILU>(x);
+    }
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_float(float x);
+template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { return (bf16_t)x; }
+#endif  // __HIPCC__
+
+}  // namespace kunlun

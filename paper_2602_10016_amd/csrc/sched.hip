@@ -1,0 +1,62 @@
+// Offsets-driven work ordering (the software tile scheduler of App. "GDPA and Fused PFFN
+// Kernel": sequence-length metadata decides the order in which work items are issued, so
+// that the long histories start first and the short ones fill the tail).
+//
+// One workgroup sorts the examples by history length, longest first, with a counting sort
+// over NBINS length buckets.  The attention kernels launch one workgroup per
+// (example, head, query tile) in that order; the hardware dispatcher hands them to compute
+// units as slots free up, which is longest-processing-time-first list scheduling.
+// Results never depend on the order: each work item is computed by exactly one wavefront.
+#include "common.h"
+
+namespace kunlun {
+
+constexpr int NBINS = 2048;
+constexpr int SCHED_THREADS = 1024;
+
+__global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(const int32_t* __restrict__ kv_off, int B,
+                                                                  int max_kv, int32_t* __restrict__ order) {
+    __shared__ int hist[NBINS];
+    __shared__ int scan[NBINS];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < NBINS; i += SCHED_THREADS) hist[i] = 0;
+    __syncthreads();
+    const int64_t span = (int64_t)max_kv + 1;
+    auto bin_of = [&](int b) {
+        int64_t len = (int64_t)kv_off[b + 1] - kv_off[b];
+        int64_t x = len * NBINS / span;
+        if (x > NBINS - 1) x = NBINS - 1;
+        if (x < 0) x = 0;
+        return NBINS - 1 - (int)x;  // bin 0 = longest
+    };
+    for (int b = tid; b < B; b += SCHED_THREADS) atomicAdd(&hist[bin_of(b)], 1);
+    __syncthreads();
+    // exclusive scan of hist (Hillis-Steele over NBINS entries, two per thread)
+    for (int i = tid; i < NBINS; i += SCHED_THREADS) scan[i] = hist[i];
+    __syncthreads();
+    for (int off = 1; off < NBINS; off <<= 1) {
+        int v0 = 0, v1 = 0;
+        const int i0 = tid, i1 = tid + SCHED_THREADS;
+        if (i0 >= off) v0 = scan[i0 - off];
+        if (i1 >= off) v1 = scan[i1 - off];
+        __syncthreads();
+        scan[i0] += v0;
+        scan[i1] += v1;
+        __syncthreads();
+    }
+    // scan is inclusive; bucket start = scan - hist.  Reuse hist as the running cursor.
+    for (int i = tid; i < NBINS; i += SCHED_THREADS) hist[i] = scan[i] - hist[i];
+    __syncthreads();
+    for (int b = tid; b < B; b += SCHED_THREADS) {
+        const int pos = atomicAdd(&hist[bin_of(b)], 1);
+        order[pos] = b;
+    }
+}
+
+hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream) {
+    if (B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, kv_off, B, max_kv, order);
+    return hipGetLastError();
+}
+
+}  // namespace kunlun

@@ -1,0 +1,44 @@
+"""Shared helpers of the GPU parity tests: upload a workload, call the C ABI through the
+binding, compare with the CPU oracle."""
+import numpy as np
+import torch
+
+TOL = {"bf16": 2e-2, "fp32": 1e-5}
+TORCH_DTYPE = {"bf16": torch.bfloat16, "fp32": torch.float32}
+
+
+def to_dev(x, dtype):
+    """fp32 numpy values (exactly representable in dtype) -> device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(x)).to(TORCH_DTYPE[dtype]).cuda()
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def offsets_dev(off):
+    return None if off is None else torch.from_numpy(np.ascontiguousarray(off, dtype=np.int32)).cuda()
+
+
+def assert_close(got, ref, tol, what=""):
+    """max-abs/rel criterion: |x - r| <= tol (1 + |r|) for every element, and the largest
+    error relative to the largest reference magnitude is below tol as well (the second clause
+    keeps the test meaningful when all values are far below 1)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values in the GPU result"
+    err = np.abs(got - ref)
+    bad = err > tol * (1.0 + np.abs(ref))
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond tol, worst {err.max():.3e}"
+    scale = np.abs(ref).max()
+    if scale > 0:
+        assert err.max() / scale <= tol, f"{what}: max err {err.max():.3e} vs max |ref| {scale:.3e} (tol {tol})"
+
+
+def assert_lse_close(got, ref, tol, what="lse"):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    inf = np.isneginf(ref)
+    assert np.array_equal(np.isneginf(got), inf), f"{what}: -inf pattern differs"
+    assert np.all(np.abs(got[~inf] - ref[~inf]) <= tol * (1.0 + np.abs(ref[~inf]))), what

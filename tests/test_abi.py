@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+that include/kunlun.h declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2602_10016_amd import build
+    build.build()
+    from paper_2602_10016_amd import binding
+    return binding
+
+
+def test_exports_match_header(kb):
+    header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
+    declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
+    assert len(declared) == 5
+    assert declared == set(kb.EXPORTS)
+    lib = kb.raw()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_and_workspace(kb):
+    assert kb.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert kb.strerror(code) not in ("ok", "unknown status")
+    assert kb.strerror(-99) == "unknown status"
+    n = kb.workspace_bytes(kb.OP_GDPA_FWD, 1024, 8, 128, 64, 4096, 65536, 1144603)
+    assert n >= 4 * 1024 and n % 256 == 0
+    assert kb.workspace_bytes(99, 1, 1, 64, 1, 1, 1, 1) == 0
+    assert kb.workspace_bytes(kb.OP_GDPA_FWD, -1, 1, 64, 1, 1, 1, 1) == 0
+
+
+def _fwd(lib, q=0x1000, k=0x1000, v=0x1000, o=0x1000, lse=None, qo=None, kvo=0x1000, B=2, H=2, d=64, max_q=8,
+         max_kv=64, total_q=16, total_kv=100, scale=0.1, act=3, head_act=None, dtype=0, ws=0x1000, ws_bytes=1 << 20):
+    vp = lambda x: None if x is None else ctypes.c_void_p(x)
+    return lib.kunlun_gdpa_fwd(vp(q), vp(k), vp(v), vp(o), vp(lse), vp(qo), vp(kvo), B, H, d, max_q, max_kv,
+                               total_q, total_kv, scale, act, head_act, dtype, vp(ws), ws_bytes, None)
+
+
+def test_gdpa_fwd_rejects_bad_arguments(kb):
+    lib = kb.raw()
+    assert _fwd(lib, q=None) == kb.ERR_NULL
+    assert _fwd(lib, o=None) == kb.ERR_NULL
+    assert _fwd(lib, kvo=None) == kb.ERR_NULL
+    assert _fwd(lib, k=None) == kb.ERR_NULL
+    assert _fwd(lib, B=-1) == kb.ERR_SHAPE
+    assert _fwd(lib, total_q=15) == kb.ERR_SHAPE          # dense Q: B * max_q rows
+    assert _fwd(lib, total_kv=-5) == kb.ERR_SHAPE
+    assert _fwd(lib, d=60) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, d=512) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, H=65) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, act=9) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, dtype=7) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, scale=float("nan")) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, head_act=(ctypes.c_int32 * 2)(3, 17)) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, q=0x1008) == kb.ERR_ALIGN
+    assert _fwd(lib, ws=0x1010) == kb.ERR_ALIGN
+    assert _fwd(lib, ws=None) == kb.ERR_WORKSPACE
+    assert _fwd(lib, ws_bytes=16) == kb.ERR_WORKSPACE
+    assert _fwd(lib, B=0, total_q=0, q=None, o=None) == kb.OK   # empty batch: nothing to do
+
+
+def test_swa_and_bwd_reject_bad_arguments(kb):
+    lib = kb.raw()
+    vp = lambda x: None if x is None else ctypes.c_void_p(x)
+    P = 0x1000
+    swa = lambda **kw: lib.kunlun_swa_fwd(vp(kw.get("q", P)), vp(P), vp(P), vp(kw.get("o", P)), None,
+                                          vp(kw.get("off", P)), kw.get("B", 2), 2, kw.get("d", 128), 100,
+                                          kw.get("total", 150), 255, 0, 0.1, kw.get("dtype", 0), vp(kw.get("ws", P)),
+                                          kw.get("ws_bytes", 1 << 20), None)
+    assert swa(q=None) == kb.ERR_NULL
+    assert swa(off=None) == kb.ERR_NULL
+    assert swa(total=-1) == kb.ERR_SHAPE
+    assert swa(d=12) == kb.ERR_UNSUPPORTED
+    assert swa(ws_bytes=0) == kb.ERR_WORKSPACE
+    assert swa(B=0) == kb.OK
+    bwd = lambda **kw: lib.kunlun_gdpa_bwd(vp(P), vp(P), vp(P), vp(kw.get("o", P)), vp(kw.get("lse", P)),
+                                           vp(kw.get("d_o", P)), vp(kw.get("dq", P)), vp(P), vp(P), None, vp(P), 2, 2,
+                                           64, 8, 64, kw.get("total_q", 16), 100, 0.1, kw.get("act", 3), None, 0,
+                                           vp(kw.get("ws", P)), 1 << 20, None)
+    assert bwd(d_o=None) == kb.ERR_NULL
+    assert bwd(dq=None) == kb.ERR_NULL
+    assert bwd(act=0, lse=None) == kb.ERR_NULL     # softmax backward needs the forward statistics
+    assert bwd(act=3, lse=None, o=None, ws=None) == kb.ERR_WORKSPACE  # no softmax head: o, lse optional
+    assert bwd(total_q=17) == kb.ERR_SHAPE
+    assert bwd(ws=None) == kb.ERR_WORKSPACE

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU fp64 oracle, element by
+element on the same seeded inputs.  bf16: max-abs/rel 2e-2; fp32: 1e-5 (see helpers.assert_close)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_10016_amd import workloads as W
+from tests.helpers import TOL, assert_close, assert_lse_close, offsets_dev, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+ACTS = {"softmax": 0, "identity": 1, "relu": 2, "gelu": 3, "gelu_tanh": 4, "silu": 5}
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2602_10016_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def run_gdpa_fwd(kb, wl, act, head_act=None, scale=None):
+    dt = wl.dtype
+    q, k, v = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt)
+    o, lse = kb.gdpa_fwd(q, k, v, offsets_dev(wl.kv_offsets), wl.scale if scale is None else scale, act,
+                         q_offsets=offsets_dev(wl.q_offsets), max_q=wl.meta.get("max_q", wl.Nq),
+                         max_kv=max(wl.max_kv, 1), head_act=head_act)
+    torch.cuda.synchronize()
+    return to_np(o), to_np(lse)
+
+
+def check_gdpa_fwd(kb, oracle, wl, act, head_act=None, scale=None):
+    scale = wl.scale if scale is None else scale
+    o, lse = run_gdpa_fwd(kb, wl, act, head_act, scale)
+    o_ref, lse_ref = oracle.gdpa_fwd(wl.q, wl.k, wl.v, wl.kv_offsets, scale, act, q_offsets=wl.q_offsets,
+                                     max_q=wl.Nq, head_act=head_act)
+    assert_close(o, o_ref, TOL[wl.dtype], f"{wl.name} O act={act}")
+    acts = head_act if head_act is not None else [act] * wl.H
+    for h, a in enumerate(acts):
+        if a == 0:
+            assert_lse_close(lse[h], lse_ref[h], 1e-2 if wl.dtype == "bf16" else 1e-5, f"{wl.name} lse h={h}")
+
+
+# ---------------- config 1: tiny fp32, dense ----------------
+
+@pytest.mark.parametrize("act", list(ACTS))
+def test_cfg1_fp32_forward(kb, oracle, act):
+    wl = W.make("cfg1", 0, softmax=(act == "softmax"))
+    check_gdpa_fwd(kb, oracle, wl, ACTS[act])
+    check_gdpa_fwd(kb, oracle, wl, ACTS[act], scale=1 / math.sqrt(wl.d))
+
+
+@pytest.mark.parametrize("act", ["softmax", "gelu", "silu", "gelu_tanh", "relu", "identity"])
+def test_cfg1_fp32_backward(kb, oracle, act):
+    wl = W.make("cfg1", 0, scale=1 / math.sqrt(32))
+    check_gdpa_bwd(kb, oracle, wl, ACTS[act])
+
+
+# ---------------- config 2: bf16 jagged GDPA forward ----------------
+
+@pytest.mark.parametrize("act", ["gelu", "softmax"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_cfg2_forward(kb, oracle, act, seed):
+    wl = W.make("cfg2", seed, softmax=(act == "softmax"))
+    check_gdpa_fwd(kb, oracle, wl, ACTS[act])
+
+
+# The weights P are rounded to bf16 before the second contraction (2^-9 relative per term), so
+# the output error is about 2^-9 * sqrt(sum_j (p_j v_j)^2).  With 1/tau scaling that is far below
+# the tolerance; the stress cases below use scores of order 1 and keep the histories short enough
+# for the absolute clause of the criterion to stay meaningful.
+@pytest.mark.parametrize("act", list(ACTS))
+@pytest.mark.parametrize("strength,lengths", [(1.0, ("uniform", 8, 96)), (3.0, ("uniform", 1, 24))])
+def test_cfg2_forward_all_activations_nonlinear_range(kb, oracle, act, strength, lengths):
+    """scale = strength/sqrt(d) puts the scores where the activations are non-linear."""
+    wl = W.make("cfg2", 2, B=48, lengths=lengths, scale=strength / math.sqrt(64))
+    check_gdpa_fwd(kb, oracle, wl, ACTS[act])
+
+
+RAGGED = [0, 1, 31, 32, 33, 63, 64, 65, 95, 97, 128, 1, 0, 200, 511, 3]
+
+
+@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 8), (64, 40), (64, 64), (128, 64), (128, 33), (128, 100), (128, 1), (64, 130)])
+@pytest.mark.parametrize("act", ["gelu", "softmax"])
+def test_ragged_tails_and_query_counts(kb, oracle, d, Nq, act):
+    wl = W.make("cfg2", 3, B=len(RAGGED), H=3, d=d, Nq=Nq, lengths=("list", RAGGED), scale=0.5 / math.sqrt(d))
+    check_gdpa_fwd(kb, oracle, wl, ACTS[act])
+
+
+def test_per_head_activations(kb, oracle):
+    head_act = [3, 0, 5, 2, 1, 4]
+    wl = W.make("cfg2", 4, B=24, H=6, lengths=("uniform", 8, 96), scale=0.125)
+    check_gdpa_fwd(kb, oracle, wl, 0, head_act=head_act)
+
+
+def test_jagged_queries(kb, oracle):
+    rng = np.random.default_rng(5)
+    B, H, d = 12, 2, 64
+    lens_q = rng.integers(0, 90, size=B)
+    wl = W.make("cfg2", 5, B=B, H=H, d=d, Nq=1, lengths=("uniform", 0, 300), scale=0.15)
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = int(lens_q.max())
+    for act in (3, 0):
+        check_gdpa_fwd(kb, oracle, wl, act)
+
+
+def test_fp32_generic_path_jagged(kb, oracle):
+    wl = W.make("cfg1", 6, B=9, H=3, d=40, Nq=5, lengths=("list", [0, 1, 63, 64, 65, 129, 300, 2, 77]),
+                scale=1 / math.sqrt(40))
+    for act in (3, 0, 5):
+        check_gdpa_fwd(kb, oracle, wl, act)
+
+
+def test_bf16_small_head_dim_uses_generic_path(kb, oracle):
+    wl = W.make("cfg2", 7, B=6, H=2, d=32, Nq=8, lengths=("list", [5, 0, 64, 100, 33, 1]), scale=0.3)
+    check_gdpa_fwd(kb, oracle, wl, 3)
+
+
+def test_examples_are_isolated_bit_exact(kb):
+    """Changing other examples' keys/values leaves an example's output bit-identical."""
+    wl = W.make("cfg2", 8, B=20, scale=0.125)
+    o1, _ = run_gdpa_fwd(kb, wl, 3)
+    b = 7
+    lo, hi = wl.kv_offsets[b], wl.kv_offsets[b + 1]
+    k2, v2 = wl.k.copy(), wl.v.copy()
+    k2[:lo] = 3.0; k2[hi:] = -2.0; v2[:lo] = 5.0; v2[hi:] = 7.0
+    wl.k, wl.v = k2, v2
+    o2, _ = run_gdpa_fwd(kb, wl, 3)
+    np.testing.assert_array_equal(o1[b * wl.Nq:(b + 1) * wl.Nq], o2[b * wl.Nq:(b + 1) * wl.Nq])
+
+
+def test_repeatable_bit_exact(kb):
+    wl = W.make("cfg2", 9, B=64)
+    a, _ = run_gdpa_fwd(kb, wl, 0)
+    b, _ = run_gdpa_fwd(kb, wl, 0)
+    np.testing.assert_array_equal(a, b)
+
+
+# ---------------- config 3: sliding window ----------------
+
+def run_swa(kb, wl, window, scale=None):
+    dt = wl.dtype
+    q, k, v = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt)
+    o, lse = kb.swa_fwd(q, k, v, offsets_dev(wl.kv_offsets), window[0], window[1],
+                        wl.scale if scale is None else scale, max_len=max(wl.max_kv, 1))
+    torch.cuda.synchronize()
+    return to_np(o), to_np(lse)
+
+
+def check_swa(kb, oracle, wl, window):
+    o, lse = run_swa(kb, wl, window)
+    o_ref, lse_ref = oracle.swa_fwd(wl.q, wl.k, wl.v, wl.kv_offsets, window[0], window[1], wl.scale)
+    assert_close(o, o_ref, TOL[wl.dtype], f"{wl.name} swa O window={window}")
+    assert_lse_close(lse, lse_ref, 1e-2 if wl.dtype == "bf16" else 1e-5)
+
+
+def test_cfg3_sliding_window(kb, oracle):
+    wl = W.make("cfg3", 0)
+    check_swa(kb, oracle, wl, wl.window)
+
+
+@pytest.mark.parametrize("window", [(255, 0), (0, 0), (3, 3), (50, 50), (100, 7), (31, 0), (32, 0), (64, 64), (-1, 0), (-1, -1), (0, -1), (1000, 1000)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_swa_windows_and_ragged_lengths(kb, oracle, window, d):
+    lens = [1, 0, 63, 64, 65, 127, 129, 300, 2, 777, 33]
+    wl = W.make("cfg3", 1, B=len(lens), H=2, d=d, lengths=("list", lens))
+    check_swa(kb, oracle, wl, window)
+
+
+def test_swa_fp32_generic(kb, oracle):
+    lens = [5, 70, 0, 131]
+    wl = W.make("cfg3", 2, B=4, H=2, d=32, dtype="fp32", sigma=1.0, lengths=("list", lens))
+    for window in [(3, 0), (2, 5), (-1, -1)]:
+        check_swa(kb, oracle, wl, window)
+
+
+def test_swa_window_covering_sequence_equals_full_attention(kb):
+    lens = [40, 100, 257]
+    wl = W.make("cfg3", 3, B=3, H=2, d=64, lengths=("list", lens))
+    a, _ = run_swa(kb, wl, (256, 256))
+    b, _ = run_swa(kb, wl, (-1, -1))
+    np.testing.assert_array_equal(a, b)
+
+
+# ---------------- config 4: large jagged GDPA forward, sampled against the oracle ----------------
+
+def device_normal(shape, sigma, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    rows = shape[0]
+    step = max(1, (1 << 27) // (shape[1] * shape[2]))
+    for s in range(0, rows, step):
+        e = min(rows, s + step)
+        out[s:e] = (torch.randn((e - s,) + tuple(shape[1:]), generator=g, device="cuda", dtype=torch.float32)
+                    * sigma).to(torch.bfloat16)
+    return out
+
+
+@pytest.mark.parametrize("act", ["gelu", "softmax"])
+def test_cfg4_full_size_sampled(kb, oracle, act):
+    """Whole workload on the GPU in the launch configuration bench.py times; the oracle
+    recomputes sampled (example, head) items: the shortest, the longest, and random ones."""
+    r = W.CONFIGS["cfg4"]
+    B, H, d, Nq = r["B"], r["H"], r["d"], r["Nq"]
+    lengths = W.make_lengths("cfg4", 0)
+    off = W.offsets_from_lengths(lengths)
+    T = int(off[-1])
+    q = device_normal((B * Nq, H, d), 0.5, 1)
+    k = device_normal((T, H, d), 0.5, 2)
+    v = device_normal((T, H, d), 0.5, 3)
+    scale = 1 / math.sqrt(d) if act == "softmax" else 1.0 / r["tau"]
+    o, lse = kb.gdpa_fwd(q, k, v, offsets_dev(off), scale, ACTS[act], max_q=Nq, max_kv=4096)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    order = np.argsort(lengths)
+    picks = list(order[:4]) + list(order[-4:]) + list(rng.choice(B, size=16, replace=False))
+    for b in picks:
+        h = int(rng.integers(H))
+        ks = slice(int(off[b]), int(off[b + 1]))
+        qs = slice(b * Nq, (b + 1) * Nq)
+        o_ref, lse_ref = oracle.gdpa_fwd(to_np(q[qs, h:h + 1]), to_np(k[ks, h:h + 1]), to_np(v[ks, h:h + 1]),
+                                         [0, lengths[b]], scale, ACTS[act], max_q=Nq)
+        assert_close(to_np(o[qs, h:h + 1]), o_ref, TOL["bf16"], f"cfg4 b={b} h={h} L={lengths[b]}")
+        if act == "softmax":
+            assert_lse_close(to_np(lse[h, qs]), lse_ref[0], 1e-2)
+    assert torch.isfinite(o.float()).all()
+
+
+# ---------------- config 5: backward ----------------
+
+def check_gdpa_bwd(kb, oracle, wl, act, head_act=None):
+    dt = wl.dtype
+    q, k, v, d_o = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt), to_dev(wl.d_o, dt)
+    kvo, qo = offsets_dev(wl.kv_offsets), offsets_dev(wl.q_offsets)
+    max_q = wl.meta.get("max_q", wl.Nq)
+    o, lse = kb.gdpa_fwd(q, k, v, kvo, wl.scale, act, q_offsets=qo, max_q=max_q, max_kv=max(wl.max_kv, 1),
+                         head_act=head_act)
+    dq, dk, dv = kb.gdpa_bwd(q, k, v, d_o, kvo, wl.scale, act, o=o, lse=lse, q_offsets=qo, max_q=max_q,
+                             max_kv=max(wl.max_kv, 1), head_act=head_act)
+    torch.cuda.synchronize()
+    dq_ref, dk_ref, dv_ref = oracle.gdpa_bwd(wl.q, wl.k, wl.v, wl.d_o, wl.kv_offsets, wl.scale, act,
+                                             q_offsets=wl.q_offsets, max_q=wl.Nq, head_act=head_act)
+    tol = TOL[dt]
+    assert_close(to_np(dq), dq_ref, tol, f"{wl.name} dQ act={act}")
+    assert_close(to_np(dk), dk_ref, tol, f"{wl.name} dK act={act}")
+    assert_close(to_np(dv), dv_ref, tol, f"{wl.name} dV act={act}")
+
+
+@pytest.mark.parametrize("act", ["gelu", "softmax"])
+def test_cfg5_backward(kb, oracle, act):
+    wl = W.make("cfg5", 0, softmax=(act == "softmax"))
+    check_gdpa_bwd(kb, oracle, wl, ACTS[act])
+
+
+@pytest.mark.parametrize("act", list(ACTS))
+@pytest.mark.parametrize("strength,lengths", [(1.0, ("uniform", 8, 96)), (3.0, ("uniform", 1, 24))])
+def test_backward_all_activations_nonlinear_range(kb, oracle, act, strength, lengths):
+    wl = W.make("cfg5", 1, B=24, lengths=lengths, scale=strength / math.sqrt(64))
+    check_gdpa_bwd(kb, oracle, wl, ACTS[act])
+
+
+@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 20), (128, 64), (128, 40), (64, 70)])
+def test_backward_ragged(kb, oracle, d, Nq):
+    wl = W.make("cfg5", 2, B=len(RAGGED), H=2, d=d, Nq=Nq, lengths=("list", RAGGED), scale=0.5 / math.sqrt(d))
+    for act in (3, 0):
+        check_gdpa_bwd(kb, oracle, wl, act)
+
+
+def test_backward_per_head_activations(kb, oracle):
+    wl = W.make("cfg5", 3, B=10, H=6, lengths=("uniform", 8, 96), scale=0.125)
+    check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
+
+
+# ---------------- degenerate calls ----------------
+
+def test_empty_batch_and_all_empty_histories(kb):
+    z = torch.zeros((0, 2, 64), dtype=torch.bfloat16, device="cuda")
+    off = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o, _ = kb.gdpa_fwd(z, z, z, off, 1.0, 3, max_q=4, max_kv=1)
+    assert o.numel() == 0
+    B, Nq = 3, 4
+    q = torch.randn((B * Nq, 2, 64), device="cuda").to(torch.bfloat16)
+    off = torch.zeros(B + 1, dtype=torch.int32, device="cuda")
+    for act in (3, 0):
+        o, lse = kb.gdpa_fwd(q, z, z, off, 1.0, act, max_q=Nq, max_kv=1)
+        torch.cuda.synchronize()
+        assert torch.all(o == 0)
+        if act == 0:
+            assert torch.all(torch.isneginf(lse))
