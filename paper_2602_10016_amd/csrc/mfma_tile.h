@@ -55,6 +55,17 @@ struct TileLayout {
         const int x = (D == 128) ? (row & 3) : ((row >> 1) & 1);
         return row * ROW_BYTES + ((((byte_in_row >> 6) ^ x)) << 6) + (byte_in_row & 63);
     }
+    // Tiles that are read BOTH ways (backward pass: K, Q, dO): one swizzle that satisfies both
+    // conditions above.  D = 128: chunk ^= 4*(row%4) + (row/4)%4;  D = 64: chunk ^= bit-reversed
+    // (row/2)%8.
+    __device__ static __forceinline__ int u_swizzle(int row) {
+        if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+        const int x = (row >> 1) & 7;
+        return ((x & 1) << 2) | (x & 2) | ((x >> 2) & 1);
+    }
+    __device__ static __forceinline__ int u_offset(int row, int byte_in_row) {
+        return row * ROW_BYTES + ((((byte_in_row >> 4) ^ u_swizzle(row))) << 4) + (byte_in_row & 15);
+    }
 };
 
 // Global -> register staging of one 32-row tile: lane l fetches 16 bytes of row
@@ -119,6 +130,39 @@ __device__ __forceinline__ bf16x8 read_vt_frag(const char* lds, int db, int c, i
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, lds + TileLayout<D>::v_offset(key0, col * 2)));
     const s16x4 hi =
         __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, lds + TileLayout<D>::v_offset(key0 + 8, col * 2)));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+// ---- the same accessors for tiles in the two-way ("u") swizzle ----
+template <int D>
+__device__ __forceinline__ void store_u_tile(char* lds, const u32x4 (&st)[TileLayout<D>::LOADS], int lane) {
+    using L = TileLayout<D>;
+    const int chunk = lane % L::CHUNKS;
+    const int rsub = lane / L::CHUNKS;
+#pragma unroll
+    for (int i = 0; i < L::LOADS; ++i) {
+        const int row = i * L::ROWS_PER_LOAD + rsub;
+        *(u32x4*)(lds + L::u_offset(row, chunk * 16)) = st[i];
+    }
+}
+
+// A (or B) operand: row `row`, contraction indices 16*kc + 8g .. +7 along the row.
+template <int D>
+__device__ __forceinline__ bf16x8 read_u_frag(const char* lds, int kc, int row, int g) {
+    return *(const bf16x8*)(lds + TileLayout<D>::u_offset(row, (2 * kc + g) * 16));
+}
+
+// Transposed operand from a row-major tile: for this lane, column col0 + (lane%32) and the
+// rows rowA .. rowA+3 (elements 0..3) and rowB .. rowB+3 (elements 4..7).  OFFSET(row, byte)
+// gives the LDS byte offset of an element.  rowA, rowB must be multiples of 4.
+template <typename OFFSET>
+__device__ __forceinline__ bf16x8 read_tr_frag(const char* lds, OFFSET offset, int rowA, int rowB, int col0, int lane) {
+    const int s = lane & 15;
+    const int col = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, lds + offset(rowA + (s >> 2), col * 2)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, lds + offset(rowB + (s >> 2), col * 2)));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     return __builtin_bit_cast(bf16x8, both);
