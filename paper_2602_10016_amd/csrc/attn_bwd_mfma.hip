@@ -245,7 +245,7 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
             for (int i = 0; i < L::LOADS; ++i) {
                 const int row = i * L::ROWS_PER_LOAD + rsub;
                 const u32x4 val = *(const u32x4*)(stage + L::k_offset(row, chunk));
-                if (row < rows_valid) *(u32x4*)(dst + row * hd + chunk * 8) = val;
+                if (row < rows_valid) __builtin_nontemporal_store(val, (u32x4*)(dst + row * hd + chunk * 8));
             }
         }
     }
@@ -288,13 +288,18 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
     }
 }
 
-// grid = B * H workgroups, examples in scheduler order (longest history first), head fastest.
+// one workgroup per (example, head), examples in scheduler order (longest history first).
 template <int D, int NQB, int NW>
 __global__ __launch_bounds__(64 * NW) void gdpa_bwd_mfma_kernel(AttnParams p) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int64_t item = blockIdx.x;
-    const int h = (int)(item % p.H);
-    const int b = p.order[item / p.H];
+    // workgroup i runs on XCD i % 8: consecutive examples go to consecutive XCDs, and each
+    // XCD walks through all heads of its examples (all L2 channels stay in use)
+    const int xcd = blockIdx.x & 7;
+    const int64_t j = blockIdx.x >> 3;
+    const int h = (int)(j % p.H);
+    const int64_t e = (j / p.H) * 8 + xcd;
+    if (e >= p.B) return;
+    const int b = p.order[e];
     const int64_t q0 = q_begin(p, b);
     const int nq = (int)(q_end(p, b) - q0);
     const int64_t k0 = p.kv_off[b];
@@ -334,7 +339,7 @@ static hipError_t launch_bwd(const AttnParams& p, hipStream_t stream) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)p.B * p.H)), dim3(64 * NW), bytes, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H)), dim3(64 * NW), bytes, stream, p);
     return hipGetLastError();
 }
 

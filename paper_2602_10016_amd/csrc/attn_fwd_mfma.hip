@@ -2,57 +2,123 @@
 // seed / context queries over a jagged history (Eq. (PMA), Eq. (seed-level attention)) and
 // sliding-window self-attention (Eq. (sliding window)).
 //
-// One wavefront = one work item = (example, head, tile of up to 32*NQB queries); a workgroup
-// is a single wavefront, so there is no barrier anywhere: every wave streams the K/V rows of
-// its own item HBM -> registers -> its private LDS tile -> MFMA operands, with the loads of
-// tile t+1 in flight while tile t is computed.  These operators do Nq flops per byte of K/V
-// (each key/value byte is used only by the queries of its own example and head), far below
-// the matrix-core ridge, so the design goal is bytes in flight, not MFMA occupancy.
+// A workgroup of NW wavefronts owns one work item = (example, head, tile of 32*NQB*NW
+// queries); each wave owns 32*NQB of those queries for the whole item.  The waves stream the
+// 32-key K/V tiles of the item together: every thread fetches its share of tile t+1 into
+// registers (whole rows, coalesced) while tile t, already in LDS, is being consumed; tiles
+// are double-buffered in LDS, so there is one barrier per tile.  These operators do only
+// Nq flops per byte of K/V (a key/value byte is used by the queries of its own example and
+// head and by nobody else), far below the matrix-core ridge, so the design goal is bytes in
+// flight and enough resident waves to hide latency, not MFMA occupancy.
 //
-// Per 32-key tile:  S^T = K Q^T (MFMA, Q^T fragments resident in registers)
-//                   P^T = score function of S^T * scale in registers (masked past the end of
-//                         the history / outside the window), packed to bf16
-//                   O^T += V^T P^T (MFMA, V^T via transposing LDS reads)
-// Softmax keeps a running maximum and sum per query (one query per lane column) and
-// rescales O^T when the maximum grows; the activation path has no such stage.
+// Per 32-key tile and wave:
+//     S^T = K Q^T              (MFMA; Q^T fragments resident in registers)
+//     P^T = score function of S^T * scale, in registers, zero past the end of the history /
+//           outside the window, packed to bf16
+//     O^T += V^T P^T           (MFMA; V^T via transposing LDS reads)
+// Softmax keeps a running maximum and sum per query (one query per lane column) and rescales
+// O^T when the maximum grows; the activation path has no such stage.
 #include "mfma_tile.h"
 
 namespace kunlun {
 
 constexpr float LOG2E = 1.4426950408889634f;
 
-template <int D, int NQB, int ACT, bool WINDOWED>
-__device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq,
-                                              int64_t t0, int64_t k0, int n_kv) {
+template <int D>
+struct FwdSmem {
+    static constexpr int TILE_BYTES = TileLayout<D>::TILE_BYTES;
+    static constexpr int BUF_BYTES = 2 * TILE_BYTES;  // K tile, then V tile
+    static constexpr int TOTAL = 2 * BUF_BYTES;       // double buffer
+};
+
+// Cooperative global -> register staging of one 32-row tile by a workgroup of 64*NW threads:
+// slot = i*64*NW + tid covers (row, 16-byte chunk) pairs row-major, so whole rows coalesce.
+template <int D, int NW>
+struct CoopTile {
     using L = TileLayout<D>;
+    static constexpr int SLOTS = KT * L::CHUNKS;
+    static constexpr int LOADS = SLOTS / (64 * NW);
+    static_assert(LOADS >= 1 && SLOTS % (64 * NW) == 0, "tile does not split evenly over the workgroup");
+
+    // STREAM: the data is read once by this workgroup and by nobody else (GDPA keys/values):
+    // non-temporal loads keep it from displacing useful lines in the caches.
+    template <bool STREAM>
+    __device__ static __forceinline__ void load(u32x4 (&st)[LOADS], const bf16_t* __restrict__ base, int64_t row_stride,
+                                                int rows_valid, int tid) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int slot = i * 64 * NW + tid;
+            int row = slot / L::CHUNKS;
+            const int chunk = slot % L::CHUNKS;
+            row = row < rows_valid ? row : rows_valid - 1;  // clamped rows get zero weight later
+            const u32x4* src = (const u32x4*)(base + row * row_stride + chunk * 8);
+            st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+        }
+    }
+    __device__ static __forceinline__ void store_k(char* lds, const u32x4 (&st)[LOADS], int tid) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int slot = i * 64 * NW + tid;
+            *(u32x4*)(lds + L::k_offset(slot / L::CHUNKS, slot % L::CHUNKS)) = st[i];
+        }
+    }
+    __device__ static __forceinline__ void store_v(char* lds, const u32x4 (&st)[LOADS], int tid) {
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i) {
+            const int slot = i * 64 * NW + tid;
+            *(u32x4*)(lds + L::v_offset(slot / L::CHUNKS, (slot % L::CHUNKS) * 16)) = st[i];
+        }
+    }
+};
+
+// One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's
+// tile; t0_wg: position of that first query inside its sequence (sliding window only).
+template <int D, int NQB, int NW, int ACT, bool WINDOWED>
+__device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq_wg,
+                                              int64_t t0_wg, int64_t k0, int n_kv) {
+    using L = TileLayout<D>;
+    using CT = CoopTile<D, NW>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16;  // contraction steps of S^T = K Q^T
     constexpr int DB = D / 32;  // 32-channel blocks of O^T
-    const int lane = threadIdx.x;
+    constexpr int QW = 32 * NQB;  // queries per wave
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
     const bf16_t* Q = (const bf16_t*)p.q;
     const bf16_t* K = (const bf16_t*)p.k + (k0 * p.H + h) * D;
     const bf16_t* V = (const bf16_t*)p.v + (k0 * p.H + h) * D;
-    char* ldsK = lds;
-    char* ldsV = lds + L::TILE_BYTES;
 
-    // key tiles this item touches
+    // this wave's queries
+    const int q_lo_w = wave * QW;
+    int nq = nq_wg - q_lo_w;
+    nq = nq < 0 ? 0 : (nq > QW ? QW : nq);
+    const bool wave_active = nq > 0;
+    const int64_t t0 = t0_wg + q_lo_w;
+
+    // key tiles of the workgroup, and of this wave
     int kt_begin = 0, kt_end = (n_kv + KT - 1) / KT;
+    int w_begin = 0, w_end = kt_end;
     if (WINDOWED && n_kv > 0) {
-        int64_t key_lo = 0, key_hi = n_kv - 1;
-        if (p.left >= 0 && t0 - p.left > key_lo) key_lo = t0 - p.left;
-        if (p.right >= 0 && t0 + nq - 1 + p.right < key_hi) key_hi = t0 + nq - 1 + p.right;
-        kt_begin = (int)(key_lo / KT);
-        kt_end = (int)(key_hi / KT) + 1;
+        int64_t lo = 0, hi = n_kv - 1;
+        if (p.left >= 0 && t0_wg - p.left > lo) lo = t0_wg - p.left;
+        if (p.right >= 0 && t0_wg + nq_wg - 1 + p.right < hi) hi = t0_wg + nq_wg - 1 + p.right;
+        kt_begin = (int)(lo / KT);
+        kt_end = (int)(hi / KT) + 1;
+        lo = 0; hi = n_kv - 1;
+        if (p.left >= 0 && t0 - p.left > lo) lo = t0 - p.left;
+        if (p.right >= 0 && t0 + nq - 1 + p.right < hi) hi = t0 + nq - 1 + p.right;
+        w_begin = (int)(lo / KT);
+        w_end = (int)(hi / KT) + 1;
     }
 
     // Q^T fragments (B operand): column = query 32*qb + r, contraction = channels 16*kc + 8g..
     bf16x8 qf[NQB][KC];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-        int qi = 32 * qb + r;
-        qi = qi < nq ? qi : nq - 1;
+        int qi = q_lo_w + 32 * qb + r;
+        qi = qi < nq_wg ? qi : nq_wg - 1;
         const bf16_t* qrow = Q + (q_row0 + qi) * hd + (int64_t)h * D + 8 * g;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *(const bf16x8*)(qrow + 16 * kc);
@@ -70,20 +136,21 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
     const float sc = SOFTMAX ? p.scale * LOG2E : p.scale;
 
-    u32x4 kst[L::LOADS], vst[L::LOADS];
-    if (kt_begin < kt_end) {
-        const int rows = n_kv - kt_begin * KT;
-        load_tile_regs<D>(kst, K + (int64_t)kt_begin * KT * hd, hd, rows, lane);
-        load_tile_regs<D>(vst, V + (int64_t)kt_begin * KT * hd, hd, rows, lane);
-    }
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        store_k_tile<D>(ldsK, kst, lane);
-        store_v_tile<D>(ldsV, vst, lane);
-        if (kt + 1 < kt_end) {
-            const int rows = n_kv - (kt + 1) * KT;
-            load_tile_regs<D>(kst, K + (int64_t)(kt + 1) * KT * hd, hd, rows, lane);
-            load_tile_regs<D>(vst, V + (int64_t)(kt + 1) * KT * hd, hd, rows, lane);
+    // Two tiles ahead are kept in flight in registers (sets A and B, used alternately) when the
+    // per-thread share of a tile is small enough; otherwise one.  The tile being consumed and
+    // the next one sit in the two LDS buffers.
+    constexpr bool PF2 = CT::LOADS <= 4;
+    constexpr int AHEAD = PF2 ? 2 : 1;
+    u32x4 kstA[CT::LOADS], vstA[CT::LOADS], kstB[CT::LOADS], vstB[CT::LOADS];
+    auto fetch = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt) {
+        if (kt < kt_end) {
+            const int rows = n_kv - kt * KT;
+            CT::template load<!WINDOWED>(ks, K + (int64_t)kt * KT * hd, hd, rows, tid);
+            CT::template load<!WINDOWED>(vs, V + (int64_t)kt * KT * hd, hd, rows, tid);
         }
+    };
+    auto compute = [&](const char* ldsK, const char* ldsV, int kt) {
+        if (!wave_active || kt < w_begin || kt >= w_end) return;
         // ---- S^T = K Q^T
         f32x16 sacc[NQB];
 #pragma unroll
@@ -167,23 +234,42 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
                 for (int qb = 0; qb < NQB; ++qb) oacc[db][qb] = mfma32(a, pf[qb][c], oacc[db][qb]);
             }
         }
+    };
+    auto step = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt, int buf) {
+        char* ldsK = lds + buf * FwdSmem<D>::BUF_BYTES;
+        char* ldsV = ldsK + L::TILE_BYTES;
+        CT::store_k(ldsK, ks, tid);
+        CT::store_v(ldsV, vs, tid);
+        // tile kt is complete in LDS; every wave is also done with the other buffer (tile kt-1)
+        if (NW > 1) __syncthreads();
+        fetch(ks, vs, kt + AHEAD);
+        compute(ldsK, ldsV, kt);
+    };
+    fetch(kstA, vstA, kt_begin);
+    if (PF2) fetch(kstB, vstB, kt_begin + 1);
+    for (int kt = kt_begin; kt < kt_end; kt += 2) {
+        step(kstA, vstA, kt, 0);
+        if (kt + 1 < kt_end) {
+            if (PF2) step(kstB, vstB, kt + 1, 1);
+            else step(kstA, vstA, kt + 1, 1);
+        }
     }
 
     // ---- epilogue: lane holds query 32*qb + r, channels 32*db + 8*(v/4) + 4g + (v%4)
     bf16_t* O = (bf16_t*)p.o;
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-        const int qi = 32 * qb + r;
+        const int qi = 32 * qb + r;  // inside this wave's block
         float inv = 1.f;
         if (SOFTMAX) {
             const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
             inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             if (p.lse && g == 0 && qi < nq)
-                p.lse[(int64_t)h * p.total_q + q_row0 + qi] =
+                p.lse[(int64_t)h * p.total_q + q_row0 + q_lo_w + qi] =
                     l_tot > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
         }
         if (qi < nq) {
-            bf16_t* orow = O + (q_row0 + qi) * hd + (int64_t)h * D + 4 * g;
+            bf16_t* orow = O + (q_row0 + q_lo_w + qi) * hd + (int64_t)h * D + 4 * g;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -197,50 +283,59 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     }
 }
 
-template <int D, int NQB, bool WINDOWED>
+template <int D, int NQB, int NW, bool WINDOWED>
 __device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds, int act, int h, int64_t q_row0,
                                                   int nq, int64_t t0, int64_t k0, int n_kv) {
     if (WINDOWED) {
-        attn_fwd_item<D, NQB, KUNLUN_ACT_SOFTMAX, true>(p, lds, h, q_row0, nq, t0, k0, n_kv);
+        attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX, true>(p, lds, h, q_row0, nq, t0, k0, n_kv);
     } else {
         switch (act) {
-        case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, KUNLUN_ACT_SOFTMAX, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, KUNLUN_ACT_IDENTITY, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, KUNLUN_ACT_RELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, KUNLUN_ACT_GELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, KUNLUN_ACT_GELU_TANH, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        default: attn_fwd_item<D, NQB, KUNLUN_ACT_SILU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_IDENTITY, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
+        default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
         }
     }
 }
 
-// GDPA / cross attention: grid = B * n_qtiles * H work items, examples in scheduler order
-// (longest history first).  item -> head fastest, then query tile, then example.
-template <int D, int NQB>
-__global__ __launch_bounds__(64) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * TileLayout<D>::TILE_BYTES];
-    const int64_t item = blockIdx.x;
-    const int h = (int)(item % p.H);
-    const int64_t e = item / p.H;
+// GDPA / cross attention: one workgroup per (example, query tile, head), examples in scheduler
+// order (longest history first).
+template <int D, int NQB, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
+    __shared__ __attribute__((aligned(1024))) char lds[FwdSmem<D>::TOTAL];
+    constexpr int QT = 32 * NQB * NW;
+    // Workgroup i runs on XCD i % 8.  Consecutive entries (example, query tile) go to
+    // consecutive XCDs and each XCD walks through all heads of its entries, so that every L2
+    // sees all address residues modulo the token stride H*D*2 (one head per XCD would use
+    // only a fraction of the L2 channels).
+    const int64_t n_entries = (int64_t)p.B * n_qtiles;
+    const int xcd = blockIdx.x & 7;
+    const int64_t j = blockIdx.x >> 3;
+    const int h = (int)(j % p.H);
+    const int64_t e = (j / p.H) * 8 + xcd;
+    if (e >= n_entries) return;
     const int qt = (int)(e % n_qtiles);
     const int b = p.order[e / n_qtiles];
     const int64_t qb0 = q_begin(p, b);
     const int64_t nq_all = q_end(p, b) - qb0;
-    const int64_t q_first = (int64_t)qt * 32 * NQB;
+    const int64_t q_first = (int64_t)qt * QT;
     if (q_first >= nq_all) return;
-    const int nq = (int)((nq_all - q_first) < 32 * NQB ? (nq_all - q_first) : 32 * NQB);
+    const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
-    attn_fwd_dispatch<D, NQB, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
+    attn_fwd_dispatch<D, NQB, NW, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
 }
 
 // Sliding-window self-attention: grid = H * (query tiles of all sequences), cut into 8
 // contiguous ranges, one per XCD (workgroup i runs on XCD i % 8), so that the query tiles of
 // one (sequence, head) - which share most of their keys - meet in the same L2.
 // tile_start[b] = number of query tiles before sequence b (written by the prefix kernel).
-template <int D, int NQB>
-__global__ __launch_bounds__(64) void swa_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
-    __shared__ __attribute__((aligned(1024))) char lds[2 * TileLayout<D>::TILE_BYTES];
+template <int D, int NQB, int NW, int OCC>
+__global__ __launch_bounds__(64 * NW, OCC) void swa_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
+    __shared__ __attribute__((aligned(1024))) char lds[FwdSmem<D>::TOTAL];
+    constexpr int QT = 32 * NQB * NW;
     const int64_t n_items = (int64_t)tile_start[p.B] * p.H;
     const int64_t per_xcd = (n_items + 7) / 8;
     const int xcd = blockIdx.x & 7;
@@ -261,9 +356,9 @@ __global__ __launch_bounds__(64) void swa_fwd_mfma_kernel(AttnParams p, const in
     const int qt = (int)(rem % nt);
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
-    const int64_t q_first = (int64_t)qt * 32 * NQB;
-    const int nq = (int)((n_kv - q_first) < 32 * NQB ? (n_kv - q_first) : 32 * NQB);
-    attn_fwd_dispatch<D, NQB, true>(p, lds, KUNLUN_ACT_SOFTMAX, h, k0 + q_first, nq, q_first, k0, n_kv);
+    const int64_t q_first = (int64_t)qt * QT;
+    const int nq = (int)((n_kv - q_first) < QT ? (n_kv - q_first) : QT);
+    attn_fwd_dispatch<D, NQB, NW, true>(p, lds, KUNLUN_ACT_SOFTMAX, h, k0 + q_first, nq, q_first, k0, n_kv);
 }
 
 // Exclusive prefix sum of ceil(len_b / tile) over the sequences, single workgroup.
@@ -295,32 +390,34 @@ bool mfma_fwd_supported(const AttnParams& p, int dtype) {
     return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128);
 }
 
-hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
-    if (p.windowed) {
-        // self-attention: 64-query tiles; an upper bound of the tile count sizes the grid
-        const int64_t max_tiles = p.total_q / 64 + p.B;
-        const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
-        const unsigned grid = (unsigned)(per_xcd * 8);
-        int32_t* tile_start = const_cast<int32_t*>(p.order);
-        hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.kv_off, p.B, 64, tile_start);
-        if (p.d == 128)
-            hipLaunchKernelGGL((swa_fwd_mfma_kernel<128, 2>), dim3(grid), dim3(64), 0, stream, p, tile_start);
-        else
-            hipLaunchKernelGGL((swa_fwd_mfma_kernel<64, 2>), dim3(grid), dim3(64), 0, stream, p, tile_start);
-        return hipGetLastError();
-    }
-    const bool one_block = p.max_q <= 32;
-    const int qtile = one_block ? 32 : 64;
-    const int n_qtiles = (p.max_q + qtile - 1) / qtile;
-    const unsigned grid = (unsigned)((int64_t)p.B * n_qtiles * p.H);
-    if (p.d == 128) {
-        if (one_block) hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<128, 1>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
-        else hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<128, 2>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
-    } else {
-        if (one_block) hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<64, 1>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
-        else hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<64, 2>), dim3(grid), dim3(64), 0, stream, p, n_qtiles);
-    }
+template <int D, int NQB, int NW, int OCC>
+static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
+    constexpr int QT = 32 * NQB * NW;
+    const int n_qtiles = (p.max_q + QT - 1) / QT;
+    const unsigned grid = (unsigned)((((int64_t)p.B * n_qtiles + 7) / 8) * 8 * p.H);
+    hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<D, NQB, NW, OCC>), dim3(grid), dim3(64 * NW), 0, stream, p, n_qtiles);
     return hipGetLastError();
+}
+
+template <int D, int NQB, int NW, int OCC>
+static hipError_t launch_swa(const AttnParams& p, hipStream_t stream) {
+    // self-attention: an upper bound of the query-tile count sizes the grid
+    constexpr int QT = 32 * NQB * NW;
+    const int64_t max_tiles = p.total_q / QT + p.B;
+    const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
+    const unsigned grid = (unsigned)(per_xcd * 8);
+    int32_t* tile_start = const_cast<int32_t*>(p.order);
+    hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.kv_off, p.B, QT, tile_start);
+    hipLaunchKernelGGL((swa_fwd_mfma_kernel<D, NQB, NW, OCC>), dim3(grid), dim3(64 * NW), 0, stream, p, tile_start);
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
+    // Two waves per workgroup, 32 queries per wave: up to 255 registers per wave, two waves
+    // per SIMD, four workgroups (128 KB of LDS) per compute unit.
+    if (p.windowed) return p.d == 128 ? launch_swa<128, 1, 2, 2>(p, stream) : launch_swa<64, 1, 2, 2>(p, stream);
+    if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
+    return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
 }
 
 }  // namespace kunlun

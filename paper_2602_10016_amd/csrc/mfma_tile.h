@@ -71,6 +71,7 @@ struct TileLayout {
 // Global -> register staging of one 32-row tile: lane l fetches 16 bytes of row
 // i*ROWS_PER_LOAD + l/CHUNKS, chunk l%CHUNKS, for i = 0..LOADS-1 (whole rows coalesced).
 // Rows past `rows_valid` are clamped to the last valid row (their weights are masked to 0).
+// Non-temporal: the rows are read once and by this wave only.
 template <int D>
 __device__ __forceinline__ void load_tile_regs(u32x4 (&st)[TileLayout<D>::LOADS], const bf16_t* __restrict__ base,
                                                int64_t row_stride, int rows_valid, int lane) {
@@ -81,7 +82,7 @@ __device__ __forceinline__ void load_tile_regs(u32x4 (&st)[TileLayout<D>::LOADS]
     for (int i = 0; i < L::LOADS; ++i) {
         int row = i * L::ROWS_PER_LOAD + rsub;
         row = row < rows_valid ? row : rows_valid - 1;
-        st[i] = *(const u32x4*)(base + row * row_stride + chunk * 8);
+        st[i] = __builtin_nontemporal_load((const u32x4*)(base + row * row_stride + chunk * 8));
     }
 }
 
