@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (untimed) so that a rocprofv3 --pmc run has a "
+                         "kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU (no collectives, no sharding); --gpus must be 1. "
@@ -107,6 +110,13 @@ def main():
              "swa_fwd": W.swa_flops(H, d, pairs)}
     nbytes = {"gdpa_fwd": W.gdpa_bytes(H, d, B * Nq, T), "gdpa_bwd": W.gdpa_bytes(H, d, B * Nq, T, backward=True),
               "swa_fwd": W.swa_bytes(H, d, T)}
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         for _, fn in calls:

@@ -24,59 +24,88 @@ namespace kunlun {
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// LDS tiles of the forward kernels: 32 rows, row-major, each row padded so that every access
+// pattern is free of bank conflicts and every offset is affine in (row, column):
+//   K rows + 16 bytes: the 16 lanes that read the same 16-byte chunk of 16 consecutive rows
+//                      (A-operand reads) fall into 16 different 16-byte bank slots;
+//   V rows + 64 bytes: the 4 consecutive rows of a transposing read fall into 4 different
+//                      64-byte bank groups.
 template <int D>
 struct FwdSmem {
-    static constexpr int TILE_BYTES = TileLayout<D>::TILE_BYTES;
-    static constexpr int BUF_BYTES = 2 * TILE_BYTES;  // K tile, then V tile
-    static constexpr int TOTAL = 2 * BUF_BYTES;       // double buffer
+    static constexpr int K_STRIDE = D * 2 + 16;
+    static constexpr int V_STRIDE = D * 2 + 64;
+    static constexpr int K_TILE = KT * K_STRIDE;
+    static constexpr int V_TILE = KT * V_STRIDE;
+    static constexpr int BUF_BYTES = K_TILE + V_TILE;  // K tile, then V tile
+    static constexpr int TOTAL = 2 * BUF_BYTES;        // double buffer
 };
 
-// Cooperative global -> register staging of one 32-row tile by a workgroup of 64*NW threads:
-// slot = i*64*NW + tid covers (row, 16-byte chunk) pairs row-major, so whole rows coalesce.
+// Cooperative global -> register -> LDS staging of one 32-row tile by a workgroup of 64*NW
+// threads: slot = i*64*NW + tid covers (row, 16-byte chunk) pairs row-major, so whole rows
+// coalesce.  A thread's chunks sit ROWS_PER_LOAD rows apart, so every address is "uniform
+// base + one per-thread offset + constant" and the key loop spends no vector arithmetic on it.
 template <int D, int NW>
 struct CoopTile {
-    using L = TileLayout<D>;
-    static constexpr int SLOTS = KT * L::CHUNKS;
+    using SM = FwdSmem<D>;
+    static constexpr int CHUNKS = D / 8;  // 16-byte chunks per row
+    static constexpr int SLOTS = KT * CHUNKS;
     static constexpr int LOADS = SLOTS / (64 * NW);
+    static constexpr int ROWS_PER_LOAD = 64 * NW / CHUNKS;
     static_assert(LOADS >= 1 && SLOTS % (64 * NW) == 0, "tile does not split evenly over the workgroup");
 
+    uint32_t goff;   // byte offset of this thread's first chunk inside a tile of the [tokens,H,D] tensor
+    int kw, vw;      // LDS byte offsets of the same chunk in the K / V tiles
+    int row0, chunk;
+    uint32_t row_bytes;
+
+    __device__ __forceinline__ void init(int tid, uint32_t row_stride_bytes) {
+        row0 = tid / CHUNKS;
+        chunk = tid % CHUNKS;
+        row_bytes = row_stride_bytes;
+        goff = (uint32_t)row0 * row_stride_bytes + chunk * 16;
+        kw = row0 * SM::K_STRIDE + chunk * 16;
+        vw = row0 * SM::V_STRIDE + chunk * 16;
+    }
     // STREAM: the data is read once by this workgroup and by nobody else (GDPA keys/values):
     // non-temporal loads keep it from displacing useful lines in the caches.
     template <bool STREAM>
-    __device__ static __forceinline__ void load(u32x4 (&st)[LOADS], const bf16_t* __restrict__ base, int64_t row_stride,
-                                                int rows_valid, int tid) {
+    __device__ __forceinline__ void load(u32x4 (&st)[LOADS], const char* __restrict__ tile_base, int rows_valid) const {
+        if (rows_valid >= KT) {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int slot = i * 64 * NW + tid;
-            int row = slot / L::CHUNKS;
-            const int chunk = slot % L::CHUNKS;
-            row = row < rows_valid ? row : rows_valid - 1;  // clamped rows get zero weight later
-            const u32x4* src = (const u32x4*)(base + row * row_stride + chunk * 8);
-            st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+            for (int i = 0; i < LOADS; ++i) {
+                const u32x4* src = (const u32x4*)(tile_base + (size_t)i * ROWS_PER_LOAD * row_bytes + goff);
+                st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+            }
+        } else {  // last tile of a history: rows past the end are clamped (they get zero weight)
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                int row = i * ROWS_PER_LOAD + row0;
+                row = row < rows_valid ? row : rows_valid - 1;
+                const u32x4* src = (const u32x4*)(tile_base + (uint32_t)row * row_bytes + chunk * 16);
+                st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+            }
         }
     }
-    __device__ static __forceinline__ void store_k(char* lds, const u32x4 (&st)[LOADS], int tid) {
+    __device__ __forceinline__ void store(char* ldsK, char* ldsV, const u32x4 (&ks)[LOADS], const u32x4 (&vs)[LOADS]) const {
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int slot = i * 64 * NW + tid;
-            *(u32x4*)(lds + L::k_offset(slot / L::CHUNKS, slot % L::CHUNKS)) = st[i];
-        }
-    }
-    __device__ static __forceinline__ void store_v(char* lds, const u32x4 (&st)[LOADS], int tid) {
+        for (int i = 0; i < LOADS; ++i) *(u32x4*)(ldsK + kw + i * ROWS_PER_LOAD * SM::K_STRIDE) = ks[i];
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int slot = i * 64 * NW + tid;
-            *(u32x4*)(lds + L::v_offset(slot / L::CHUNKS, (slot % L::CHUNKS) * 16)) = st[i];
-        }
+        for (int i = 0; i < LOADS; ++i) *(u32x4*)(ldsV + vw + i * ROWS_PER_LOAD * SM::V_STRIDE) = vs[i];
     }
 };
+
+// Largest growth of a row maximum (log2 units) that is tolerated before the running
+// reference of the online softmax is moved: weights stay below 2^8, and the accumulators are
+// rescaled only when some query of the wave exceeds it.  The result is unchanged in exact
+// arithmetic because numerator and denominator use the same reference.
+constexpr float SOFTMAX_LAZY_LOG2 = 8.f;
 
 // One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's
 // tile; t0_wg: position of that first query inside its sequence (sliding window only).
 template <int D, int NQB, int NW, int ACT, bool WINDOWED>
 __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq_wg,
                                               int64_t t0_wg, int64_t k0, int n_kv) {
-    using L = TileLayout<D>;
+    using SM = FwdSmem<D>;
     using CT = CoopTile<D, NW>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16;  // contraction steps of S^T = K Q^T
@@ -86,9 +115,11 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
+    const uint32_t row_bytes = (uint32_t)(hd * 2);
+    const int64_t tile_bytes = (int64_t)KT * row_bytes;
     const bf16_t* Q = (const bf16_t*)p.q;
-    const bf16_t* K = (const bf16_t*)p.k + (k0 * p.H + h) * D;
-    const bf16_t* V = (const bf16_t*)p.v + (k0 * p.H + h) * D;
+    const char* K = (const char*)((const bf16_t*)p.k + (k0 * p.H + h) * D);
+    const char* V = (const char*)((const bf16_t*)p.v + (k0 * p.H + h) * D);
 
     // this wave's queries
     const int q_lo_w = wave * QW;
@@ -113,6 +144,17 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         w_end = (int)(hi / KT) + 1;
     }
 
+    CT ct;
+    ct.init(tid, row_bytes);
+    // LDS read offsets of this lane.  K fragment of contraction step kc (A operand: row r,
+    // channels 16*kc + 8g ..): kr + 32*kc.  V^T fragment of channel block db for the keys in
+    // registers 8c..8c+7 of the score layout (keys 16c + 4g + 0..3 and 16c + 8 + 4g + 0..3): two
+    // transposing reads at vr + 64*db + 16c rows (+ 8 rows); in each, the 16 lanes of a group
+    // address a 4 (keys) x 16 (channels) block - lane s points at key s/4, channels 4*(s%4) .. -
+    // and lane i receives channel i of the four keys.
+    const int kr = r * SM::K_STRIDE + g * 16;
+    const int vr = (4 * g + ((lane & 15) >> 2)) * SM::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+
     // Q^T fragments (B operand): column = query 32*qb + r, contraction = channels 16*kc + 8g..
     bf16x8 qf[NQB][KC];
 #pragma unroll
@@ -131,22 +173,21 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) oacc[db][qb][v] = 0.f;
-    float m_run[NQB], l_run[NQB];
+    float m_ref[NQB], l_run[NQB];  // softmax: reference maximum (log2 units) and running sum
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) { m_run[qb] = -INFINITY; l_run[qb] = 0.f; }
+    for (int qb = 0; qb < NQB; ++qb) { m_ref[qb] = -INFINITY; l_run[qb] = 0.f; }
     const float sc = SOFTMAX ? p.scale * LOG2E : p.scale;
 
-    // Two tiles ahead are kept in flight in registers (sets A and B, used alternately) when the
-    // per-thread share of a tile is small enough; otherwise one.  The tile being consumed and
-    // the next one sit in the two LDS buffers.
-    constexpr bool PF2 = CT::LOADS <= 4;
+    // Tiles ahead of the one being consumed are in flight in registers: two (sets A and B,
+    // used alternately) for streamed keys when the per-thread share is small enough, else one.
+    constexpr bool PF2 = !WINDOWED && CT::LOADS <= 4;
     constexpr int AHEAD = PF2 ? 2 : 1;
     u32x4 kstA[CT::LOADS], vstA[CT::LOADS], kstB[CT::LOADS], vstB[CT::LOADS];
     auto fetch = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt) {
         if (kt < kt_end) {
             const int rows = n_kv - kt * KT;
-            CT::template load<!WINDOWED>(ks, K + (int64_t)kt * KT * hd, hd, rows, tid);
-            CT::template load<!WINDOWED>(vs, V + (int64_t)kt * KT * hd, hd, rows, tid);
+            ct.template load<!WINDOWED>(ks, K + kt * tile_bytes, rows);
+            ct.template load<!WINDOWED>(vs, V + kt * tile_bytes, rows);
         }
     };
     auto compute = [&](const char* ldsK, const char* ldsV, int kt) {
@@ -159,7 +200,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
             for (int v = 0; v < 16; ++v) sacc[qb][v] = 0.f;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const bf16x8 a = read_k_frag<D>(ldsK, kc, r, g);
+            const bf16x8 a = *(const bf16x8*)(ldsK + kr + 32 * kc);
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb) sacc[qb] = mfma32(a, qf[qb][kc], sacc[qb]);
         }
@@ -175,49 +216,56 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         bf16x8 pf[NQB][2];
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
-            float pv[16];  // scaled scores, then weights
-            if (need_mask) {
-                const int64_t tq = t0 + 32 * qb + r;
+            float pv[16];  // raw scores, then weights
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t key = key_base + c_row(v, g);
-                    bool ok = key < n_kv;
-                    if (WINDOWED) {
-                        if (p.left >= 0 && key < tq - p.left) ok = false;
-                        if (p.right >= 0 && key > tq + p.right) ok = false;
-                    }
-                    const float s = sacc[qb][v] * sc;
-                    if (SOFTMAX) pv[v] = ok ? s : -INFINITY;
-                    else pv[v] = ok ? act_fast<ACT>(s) : 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float s = sacc[qb][v] * sc;
-                    pv[v] = SOFTMAX ? s : act_fast<ACT>(s);
-                }
-            }
+            for (int v = 0; v < 16; ++v) pv[v] = sacc[qb][v];
             if (SOFTMAX) {
-                // scores are in log2 units (scale * log2 e folded into sc)
+                if (need_mask) {
+                    const int64_t tq = t0 + 32 * qb + r;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int64_t key = key_base + c_row(v, g);
+                        bool ok = key < n_kv;
+                        if (WINDOWED) {
+                            if (p.left >= 0 && key < tq - p.left) ok = false;
+                            if (p.right >= 0 && key > tq + p.right) ok = false;
+                        }
+                        pv[v] = ok ? pv[v] : -INFINITY;
+                    }
+                }
+                // scale > 0 (checked on the host), so the maximum commutes with the scaling;
+                // scores are handled in log2 units (scale * log2 e folded into sc)
                 float mx = pv[0];
 #pragma unroll
                 for (int v = 1; v < 16; ++v) mx = fmaxf(mx, pv[v]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // the other lane half holds the other 16 keys
-                const float m_new = fmaxf(m_run[qb], mx);
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float corr = fast_exp2(m_run[qb] - m_safe);
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;  // the other lane half holds the other 16 keys
+                const bool grow = mx > m_ref[qb] + SOFTMAX_LAZY_LOG2;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                    const float corr = grow ? fast_exp2(m_ref[qb] - mx) : 1.f;
+                    m_ref[qb] = grow ? mx : m_ref[qb];
+                    l_run[qb] *= corr;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= corr;
+                }
+                const float neg_m = m_ref[qb] == -INFINITY ? 0.f : -m_ref[qb];
                 float sum = 0.f;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    pv[v] = fast_exp2(pv[v] - m_safe);
+                    pv[v] = fast_exp2(fmaf(pv[v], sc, neg_m));
                     sum += pv[v];
                 }
-                l_run[qb] = l_run[qb] * corr + sum;
-                m_run[qb] = m_new;
+                l_run[qb] += sum;
+            } else if (need_mask) {
 #pragma unroll
-                for (int db = 0; db < DB; ++db)
+                for (int v = 0; v < 16; ++v) {
+                    const bool ok = key_base + c_row(v, g) < n_kv;
+                    pv[v] = ok ? act_fast<ACT>(pv[v] * sc) : 0.f;
+                }
+            } else {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= corr;
+                for (int v = 0; v < 16; ++v) pv[v] = act_fast<ACT>(pv[v] * sc);
             }
 #pragma unroll
             for (int c = 0; c < 2; ++c)
@@ -229,17 +277,20 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                const bf16x8 a = read_vt_frag<D>(ldsV, db, c, lane);
+                const char* src = ldsV + vr + 64 * db + c * 16 * SM::V_STRIDE;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * SM::V_STRIDE));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const bf16x8 a = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int qb = 0; qb < NQB; ++qb) oacc[db][qb] = mfma32(a, pf[qb][c], oacc[db][qb]);
             }
         }
     };
     auto step = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt, int buf) {
-        char* ldsK = lds + buf * FwdSmem<D>::BUF_BYTES;
-        char* ldsV = ldsK + L::TILE_BYTES;
-        CT::store_k(ldsK, ks, tid);
-        CT::store_v(ldsV, vs, tid);
+        char* ldsK = lds + buf * SM::BUF_BYTES;
+        char* ldsV = ldsK + SM::K_TILE;
+        ct.store(ldsK, ldsV, ks, vs);
         // tile kt is complete in LDS; every wave is also done with the other buffer (tile kt-1)
         if (NW > 1) __syncthreads();
         fetch(ks, vs, kt + AHEAD);
@@ -256,6 +307,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     }
 
     // ---- epilogue: lane holds query 32*qb + r, channels 32*db + 8*(v/4) + 4g + (v%4)
+    if (!wave_active) return;
     bf16_t* O = (bf16_t*)p.o;
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
@@ -266,7 +318,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
             inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             if (p.lse && g == 0 && qi < nq)
                 p.lse[(int64_t)h * p.total_q + q_row0 + q_lo_w + qi] =
-                    l_tot > 0.f ? (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
+                    l_tot > 0.f ? (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
         }
         if (qi < nq) {
             bf16_t* orow = O + (q_row0 + q_lo_w + qi) * hd + (int64_t)h * D + 4 * g;
@@ -387,7 +439,12 @@ __global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __rest
 }
 
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
-    return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128);
+    if (dtype != KUNLUN_BF16 || (p.d != 64 && p.d != 128)) return false;
+    // the online softmax takes the row maximum before scaling: it needs scale > 0
+    // (other scales are served by the generic kernels)
+    for (int h = 0; h < p.H; ++h)
+        if (p.head_act[h] == KUNLUN_ACT_SOFTMAX && !(p.scale > 0.f)) return false;
+    return true;
 }
 
 template <int D, int NQB, int NW, int OCC>
