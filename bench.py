@@ -28,12 +28,13 @@ MFMA_BF16_PEAK = 2.5e15   # MI355X dense bf16, FLOP/s
 HBM_PEAK = 8.0e12         # B/s
 WORKLOAD = "cfg4"
 WINDOW = (255, 0)
-ORACLE_SAMPLE_EXAMPLES = 48
+ORACLE_SAMPLE_EXAMPLES = 256
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled by the same counters on a copy kernel of known size; None until measured for a kernel
-# (see profiles/).  Keyed by breakdown name.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch (bytes) from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch), each scaled by what the same counter read for the 1 GiB
+# device-to-device copy of --copy-calibration (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see
+# profiles/bench_cfg4_hbm_traffic.txt.  Valid for the default workload and seed only.
+MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957652000, "gdpa_bwd": 9780100000, "swa_fwd": 10763900000}
 
 
 def device_normal(torch, shape, sigma, seed):
@@ -151,7 +152,9 @@ def main():
     dom = max(call_ms, key=call_ms.get)
     achieved = nbytes[dom] / (call_ms[dom] * 1e-3) / 1e9
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": round(achieved / (HBM_PEAK / 1e9), 4), "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
+                "frac": round(achieved / (HBM_PEAK / 1e9), 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if args.seed == 0 else None,
+                "algorithmic_bytes": int(nbytes[dom])}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

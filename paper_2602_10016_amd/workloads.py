@@ -152,10 +152,12 @@ def gdpa_flops(H: int, d: int, Nq: int, T: int, backward: bool = False) -> float
     return (10.0 if backward else 4.0) * d * H * Nq * T
 
 
-def gdpa_bytes(H: int, d: int, total_q: int, T: int, elt: int = 2, backward: bool = False) -> float:
-    """Forward: K, V read once, Q read, O written.  Backward: Q, K, V, dO read; dQ, dK, dV written."""
+def gdpa_bytes(H: int, d: int, total_q: int, T: int, elt: int = 2, backward: bool = False,
+               softmax: bool = False) -> float:
+    """Forward: K, V read once, Q read, O written.  Backward: K, V, Q, dO read; dK, dV, dQ written
+    (softmax heads also read O, and LSE which is not counted)."""
     if backward:
-        return float(elt) * (4.0 * T * H * d + 4.0 * total_q * H * d)
+        return float(elt) * (4.0 * T * H * d + (4.0 if softmax else 3.0) * total_q * H * d)
     return float(elt) * (2.0 * T * H * d + 2.0 * total_q * H * d)
 
 
