@@ -66,25 +66,19 @@ struct CoopTile {
         kw = row0 * SM::K_STRIDE + chunk * 16;
         vw = row0 * SM::V_STRIDE + chunk * 16;
     }
+    // Loads go through a buffer resource that covers exactly the valid rows of the tile: rows
+    // past the end of a history read as zero (and get zero weight later), with no address
+    // clamping in the loop.  voffset = the thread's constant offset, soffset = uniform.
     // STREAM: the data is read once by this workgroup and by nobody else (GDPA keys/values):
     // non-temporal loads keep it from displacing useful lines in the caches.
     template <bool STREAM>
     __device__ __forceinline__ void load(u32x4 (&st)[LOADS], const char* __restrict__ tile_base, int rows_valid) const {
-        if (rows_valid >= KT) {
+        const int rows = rows_valid < KT ? rows_valid : KT;
+        const int bytes = (rows - 1) * (int)row_bytes + D * 2;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tile_base, 0, bytes, 0x00020000);
 #pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
-                const u32x4* src = (const u32x4*)(tile_base + (size_t)i * ROWS_PER_LOAD * row_bytes + goff);
-                st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
-            }
-        } else {  // last tile of a history: rows past the end are clamped (they get zero weight)
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i) {
-                int row = i * ROWS_PER_LOAD + row0;
-                row = row < rows_valid ? row : rows_valid - 1;
-                const u32x4* src = (const u32x4*)(tile_base + (uint32_t)row * row_bytes + chunk * 16);
-                st[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
-            }
-        }
+        for (int i = 0; i < LOADS; ++i)
+            st[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff, i * ROWS_PER_LOAD * row_bytes, STREAM ? 2 : 0);
     }
     __device__ __forceinline__ void store(char* ldsK, char* ldsV, const u32x4 (&ks)[LOADS], const u32x4 (&vs)[LOADS]) const {
 #pragma unroll
@@ -166,6 +160,23 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *(const bf16x8*)(qrow + 16 * kc);
     }
 
+    // visible keys of this lane's query: key_lo .. key_lo + key_span (an empty range for padding
+    // lanes whose query lies past the end)
+    int key_lo[NQB];
+    unsigned key_span[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const int tq = (int)t0 + 32 * qb + r;
+        int lo = 0, hi = n_kv - 1;
+        if (WINDOWED) {
+            if (p.left >= 0 && tq - p.left > lo) lo = tq - p.left;
+            if (p.right >= 0 && tq + p.right < hi) hi = tq + p.right;
+        }
+        const bool empty = hi < lo;
+        key_lo[qb] = empty ? 0x3fffffff : lo;
+        key_span[qb] = empty ? 0u : (unsigned)(hi - lo);
+    }
+
     f32x16 oacc[DB][NQB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -209,7 +220,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         bool need_mask = key_base + KT > n_kv;
         if (WINDOWED) {
             // interior tile: every (valid query, key) pair of the tile is inside the window
-            const int64_t tq_lo = t0, tq_hi = t0 + nq - 1;
+            const int tq_lo = (int)t0, tq_hi = (int)t0 + nq - 1;
             if (p.left >= 0 && key_base < tq_hi - p.left) need_mask = true;
             if (p.right >= 0 && key_base + KT - 1 > tq_lo + p.right) need_mask = true;
         }
@@ -219,17 +230,13 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
             float pv[16];  // raw scores, then weights
 #pragma unroll
             for (int v = 0; v < 16; ++v) pv[v] = sacc[qb][v];
+            // key k of this lane's query is visible iff (unsigned)(k - key_lo) <= key_span
+            const unsigned rel0 = (unsigned)(key_base + 4 * g - key_lo[qb]);
             if (SOFTMAX) {
                 if (need_mask) {
-                    const int64_t tq = t0 + 32 * qb + r;
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int64_t key = key_base + c_row(v, g);
-                        bool ok = key < n_kv;
-                        if (WINDOWED) {
-                            if (p.left >= 0 && key < tq - p.left) ok = false;
-                            if (p.right >= 0 && key > tq + p.right) ok = false;
-                        }
+                        const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span[qb];
                         pv[v] = ok ? pv[v] : -INFINITY;
                     }
                 }
@@ -260,8 +267,9 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
             } else if (need_mask) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const bool ok = key_base + c_row(v, g) < n_kv;
-                    pv[v] = ok ? act_fast<ACT>(pv[v] * sc) : 0.f;
+                    const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span[qb];
+                    const float w = act_fast<ACT>(pv[v] * sc);
+                    pv[v] = ok ? w : 0.f;
                 }
             } else {
 #pragma unroll
