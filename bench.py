@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--skip-other-configs", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (untimed) so that a rocprofv3 --pmc run has a "
                          "kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -156,6 +157,43 @@ def main():
                 "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if args.seed == 0 else None,
                 "algorithmic_bytes": int(nbytes[dom])}
 
+    # The other the benchmark spec workloads (parity-test cases, small): one timed call each, untimed
+    # with respect to `value`; reported for their achieved HBM GB/s (inputs fit the 256 MB
+    # Infinity Cache, so these are warm-cache figures).
+    other = {}
+    if not args.skip_other_configs:
+        def timed(fn, n=20):
+            for _ in range(3):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(n):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / n
+        dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).cuda()
+        w2 = W.make("cfg2", args.seed)
+        q2, k2, v2, do2 = dev(w2.q), dev(w2.k), dev(w2.v), dev(w2.d_o)
+        off2 = torch.from_numpy(w2.kv_offsets).cuda()
+        o2 = torch.empty_like(q2)
+        wsx = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+        ms = timed(lambda: kb.gdpa_fwd(q2, k2, v2, off2, w2.scale, act, max_q=w2.Nq, max_kv=1024, out=o2, want_lse=False, workspace=wsx))
+        by, fl = W.gdpa_bytes(w2.H, w2.d, w2.total_q, w2.total_kv), W.gdpa_flops(w2.H, w2.d, w2.Nq, w2.total_kv)
+        other["cfg2_gdpa_fwd"] = {"us": round(ms * 1e3, 1), "gbps": round(by / ms / 1e6, 1), "tflops": round(fl / ms / 1e9, 1)}
+        ms = timed(lambda: kb.gdpa_bwd(q2, k2, v2, do2, off2, w2.scale, act, max_q=w2.Nq, max_kv=1024, workspace=wsx))
+        by = W.gdpa_bytes(w2.H, w2.d, w2.total_q, w2.total_kv, backward=True)
+        fl = W.gdpa_flops(w2.H, w2.d, w2.Nq, w2.total_kv, backward=True)
+        other["cfg5_gdpa_bwd"] = {"us": round(ms * 1e3, 1), "gbps": round(by / ms / 1e6, 1), "tflops": round(fl / ms / 1e9, 1)}
+        w3 = W.make("cfg3", args.seed)
+        q3, k3, v3 = dev(w3.q), dev(w3.k), dev(w3.v)
+        off3 = torch.from_numpy(w3.kv_offsets).cuda()
+        o3 = torch.empty_like(q3)
+        ms = timed(lambda: kb.swa_fwd(q3, k3, v3, off3, w3.window[0], w3.window[1], w3.scale, max_len=2048, out=o3, want_lse=False, workspace=wsx))
+        by, fl = W.swa_bytes(w3.H, w3.d, w3.total_kv), W.swa_flops(w3.H, w3.d, W.swa_pairs(w3.lengths, *w3.window))
+        other["cfg3_swa_fwd"] = {"us": round(ms * 1e3, 1), "gbps": round(by / ms / 1e6, 1), "tflops": round(fl / ms / 1e9, 1)}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -186,7 +224,7 @@ def main():
                                f"sigma 1) clipped [32,4096], T={T} tokens; step = gdpa_fwd(gelu, 1/tau) + gdpa_bwd + "
                                f"swa_fwd(window 256 causal) on the same batch", "seed": args.seed,
                    "step_gflop": round(total_flops / 1e9, 1)},
-        "breakdown": breakdown, "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "breakdown": breakdown, "roofline": roofline, "cpu_baseline": cpu_baseline, "other_configs": other,
     }
     print(json.dumps(out))
 

@@ -99,9 +99,14 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
     hipError_t e;
     if (mfma_fwd_supported(p, dtype)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
-        p.order = order;
-        e = launch_schedule(kv_offsets, B, max_kv, order, s);
-        if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        const int64_t wgs = (int64_t)B * H * ((max_q + 63) / 64);
+        if (schedule_is_moot(wgs, 4)) {  // every forward kernel fits 4 workgroups per compute unit
+            p.order = nullptr;
+        } else {
+            p.order = order;
+            e = launch_schedule(kv_offsets, B, max_kv, order, s);
+            if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        }
         e = launch_mfma_fwd(p, s);
     } else {
         e = launch_scalar_fwd(p, dtype, s);
@@ -144,9 +149,13 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
     hipError_t e;
     if (mfma_bwd_supported(p, dtype)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
-        p.order = order;
-        e = launch_schedule(kv_offsets, B, max_kv, order, s);
-        if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        if (schedule_is_moot((int64_t)B * H, d == 128 ? 1 : 4)) {  // d=128: one 128 KB workgroup per compute unit
+            p.order = nullptr;
+        } else {
+            p.order = order;
+            e = launch_schedule(kv_offsets, B, max_kv, order, s);
+            if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        }
         e = launch_mfma_bwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
     } else {
         e = launch_scalar_bwd(p, dtype, s);

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(64 * NW) void gdpa_bwd_mfma_kernel(AttnParams p) {
     const int h = (int)(j % p.H);
     const int64_t e = (j / p.H) * 8 + xcd;
     if (e >= p.B) return;
-    const int b = p.order[e];
+    const int b = p.order ? p.order[e] : (int)e;
     const int64_t q0 = q_begin(p, b);
     const int nq = (int)(q_end(p, b) - q0);
     const int64_t k0 = p.kv_off[b];

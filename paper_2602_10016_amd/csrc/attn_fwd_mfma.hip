@@ -377,7 +377,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
     const int64_t e = (j / p.H) * 8 + xcd;
     if (e >= n_entries) return;
     const int qt = (int)(e % n_qtiles);
-    const int b = p.order[e / n_qtiles];
+    const int b = p.order ? p.order[e / n_qtiles] : (int)(e / n_qtiles);
     const int64_t qb0 = q_begin(p, b);
     const int64_t nq_all = q_end(p, b) - qb0;
     const int64_t q_first = (int64_t)qt * QT;
@@ -478,9 +478,9 @@ static hipError_t launch_swa(const AttnParams& p, hipStream_t stream) {
 }
 
 hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
-    // Two waves per workgroup, 32 queries per wave: up to 255 registers per wave, two waves
-    // per SIMD, four workgroups (128 KB of LDS) per compute unit.
-    if (p.windowed) return p.d == 128 ? launch_swa<128, 1, 2, 2>(p, stream) : launch_swa<64, 1, 2, 2>(p, stream);
+    // 32 queries per wave, up to 255 registers per wave, two waves per SIMD.
+    // sliding window: 128-query tiles (4 waves) - fewer K/V tile loads per query than 64
+    if (p.windowed) return p.d == 128 ? launch_swa<128, 1, 4, 2>(p, stream) : launch_swa<64, 1, 4, 2>(p, stream);
     if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
     return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
 }

@@ -22,7 +22,7 @@ struct AttnParams {
     void* dv;
     const int32_t* q_off;   // null: dense queries, max_q rows per example
     const int32_t* kv_off;
-    const int32_t* order;   // examples, longest history first (written by the scheduler kernel)
+    const int32_t* order;   // examples, longest history first (written by the scheduler kernel); null: 0..B-1
     int B, H, d, max_q, max_kv;
     int64_t total_q, total_kv;
     float scale;
@@ -36,6 +36,10 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
+// True when the launch is so small that every workgroup is resident at once (wgs_per_cu = how
+// many workgroups of the kernel fit one compute unit): the issue order then has no effect and
+// the sorting kernel is skipped.
+bool schedule_is_moot(int64_t workgroups, int wgs_per_cu);
 hipError_t launch_scalar_fwd(const AttnParams& p, int dtype, hipStream_t stream);
 hipError_t launch_scalar_bwd(const AttnParams& p, int dtype, hipStream_t stream);
 bool mfma_fwd_supported(const AttnParams& p, int dtype);

@@ -53,6 +53,9 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(const int32_t* 
     }
 }
 
+// MI355X has 256 compute units.
+bool schedule_is_moot(int64_t workgroups, int wgs_per_cu) { return workgroups <= (int64_t)wgs_per_cu * 256; }
+
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream) {
     if (B <= 0) return hipSuccess;
     hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, kv_off, B, max_kv, order);
