@@ -1,7 +1,7 @@
 /*
  * kunlun.h - C ABI of the Kunlun attention library for AMD Instinct MI355X (gfx950).
  *
- * Three operators of the Kunlun architecture (arXiv 2602.10016) as fused, jagged-aware
+ * The attention operators of the Kunlun architecture (arXiv 2602.10016) as fused, jagged-aware
  * GPU kernels:
  *
  *   kunlun_gdpa_fwd  Generalized Dot-Product Attention, Eq. (GDPA) of Sec. "Multi-Head
@@ -19,6 +19,7 @@
  *   kunlun_swa_fwd   Sliding-window self-attention, Eq. (sliding window) of Sec. "Sliding
  *                    Window Attention": query t attends to keys [t-left, t+right] of its
  *                    own sequence under softmax.
+ *   kunlun_swa_bwd   Gradient of <O, dO> of the same with respect to Q, K, V.
  *
  * Jagged layout.  A batch holds B examples.  Tensors are packed "tokens, heads, channels":
  *   Q  [total_q,  H, d]      O, dO, dQ like Q
@@ -80,7 +81,7 @@ typedef enum {
     KUNLUN_ACT_SILU = 5
 } kunlun_act;
 
-typedef enum { KUNLUN_OP_GDPA_FWD = 0, KUNLUN_OP_GDPA_BWD = 1, KUNLUN_OP_SWA_FWD = 2 } kunlun_op;
+typedef enum { KUNLUN_OP_GDPA_FWD = 0, KUNLUN_OP_GDPA_BWD = 1, KUNLUN_OP_SWA_FWD = 2, KUNLUN_OP_SWA_BWD = 3 } kunlun_op;
 
 #define KUNLUN_MAX_HEADS 64
 
@@ -130,9 +131,22 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
                    int H, int d, int max_len, int64_t total, int window_left, int window_right, float scale,
                    int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Backward of kunlun_swa_fwd (Eq. (sliding window)): dq, dk, dv (out, device, shaped like q,
+ * fully overwritten) from q, k, v, the forward results o and lse (in, device, both required)
+ * and the upstream gradient d_o.  With p = exp(s - lse) the weight of an in-window (query,
+ * key) pair and dp = <dO_row, V_row>:  dV += p dO;  ds = p (dp - rowsum(dO * O)) scale;
+ * dQ += ds K;  dK += ds Q.  A key collects contributions from the queries t with
+ * t - window_left <= key <= t + window_right.  Other arguments as in kunlun_swa_fwd.
+ */
+int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                   void* dq, void* dk, void* dv, const int32_t* offsets, int B, int H, int d, int max_len,
+                   int64_t total, int window_left, int window_right, float scale, int dtype, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace that a call of `op` (kunlun_op) with these sizes needs.  Returns 0 for
- * an unknown op or negative sizes.  For KUNLUN_OP_SWA_FWD pass max_len as max_q and max_kv
- * and total as total_q and total_kv. */
+ * an unknown op or negative sizes.  For the sliding-window ops pass max_len as max_q and
+ * max_kv and total as total_q and total_kv. */
 size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
                               int64_t total_kv);
 

@@ -20,8 +20,9 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
-OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD = 0, 1, 2
-EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_workspace_bytes", "kunlun_strerror"]
+OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
+EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
+           "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -32,6 +33,9 @@ _lib.kunlun_gdpa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _v
 _lib.kunlun_gdpa_bwd.restype = _i
 _lib.kunlun_swa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _i, _i, _f, _i, _vp, _sz, _vp]
 _lib.kunlun_swa_fwd.restype = _i
+_lib.kunlun_swa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _i, _i, _f, _i, _vp,
+                                _sz, _vp]
+_lib.kunlun_swa_bwd.restype = _i
 _lib.kunlun_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i, _i64, _i64]
 _lib.kunlun_workspace_bytes.restype = _sz
 _lib.kunlun_strerror.argtypes = [_i]
@@ -144,3 +148,19 @@ def swa_fwd(q, k, v, offsets, window_left, window_right, scale, *, max_len, out=
     if rc != OK:
         raise KunlunError(rc)
     return o, lse
+
+
+def swa_bwd(q, k, v, o, lse, d_o, offsets, window_left, window_right, scale, *, max_len, workspace=None,
+            stream=None):
+    """kunlun_swa_bwd.  o and lse are the results of swa_fwd.  Returns (dq, dk, dv)."""
+    total, H, d = q.shape
+    B = offsets.numel() - 1
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    nbytes = workspace_bytes(OP_SWA_BWD, B, H, d, max_len, max_len, total, total)
+    ws = _workspace(workspace, nbytes, q.device)
+    rc = _lib.kunlun_swa_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
+                             _ptr(offsets), B, H, d, int(max_len), total, int(window_left), int(window_right),
+                             float(scale), _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return dq, dk, dv

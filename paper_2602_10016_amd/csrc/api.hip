@@ -47,6 +47,7 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
     switch (op) {
     case KUNLUN_OP_GDPA_FWD:
     case KUNLUN_OP_SWA_FWD:
+    case KUNLUN_OP_SWA_BWD:
         return WS_HEADER_BYTES + order_bytes(B);
     case KUNLUN_OP_GDPA_BWD:
         return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_workspace_tail(B, H, d, max_q, total_q);
@@ -195,6 +196,38 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
     } else {
         e = launch_scalar_fwd(p, dtype, s);
     }
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
+int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                   void* dq, void* dk, void* dv, const int32_t* offsets, int B, int H, int d, int max_len,
+                   int64_t total, int window_left, int window_right, float scale, int dtype, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    int rc = check_common(B, H, d, max_len, max_len, total, total, scale, dtype);
+    if (rc != KUNLUN_OK) return rc;
+    if (B == 0 || total == 0) return KUNLUN_OK;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !offsets) return KUNLUN_ERR_NULL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16) || !aligned(d_o, 16) ||
+        !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lse, 4) || !aligned(offsets, 4))
+        return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_SWA_BWD, B, H, d, max_len, max_len, total, total))
+        return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+
+    AttnParams p;
+    std::memset(&p, 0, sizeof(p));
+    for (int h = 0; h < H; ++h) p.head_act[h] = KUNLUN_ACT_SOFTMAX;
+    p.q = q; p.k = k; p.v = v; p.o = const_cast<void*>(o); p.lse = const_cast<float*>(lse); p.d_o = d_o;
+    p.dq = dq; p.dk = dk; p.dv = dv;
+    p.q_off = offsets; p.kv_off = offsets;
+    p.B = B; p.H = H; p.d = d; p.max_q = max_len; p.max_kv = max_len;
+    p.total_q = total; p.total_kv = total; p.scale = scale;
+    p.windowed = 1;
+    p.left = window_left < 0 ? -1 : window_left;
+    p.right = window_right < 0 ? -1 : window_right;
+    // one wavefront per gradient row (generic kernels): dQ rows over their windows, then dK/dV
+    // rows over the queries that see them
+    const hipError_t e = launch_scalar_bwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 

@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 5
+    assert len(declared) == 6
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
@@ -82,6 +82,15 @@ def test_swa_and_bwd_reject_bad_arguments(kb):
     assert swa(d=12) == kb.ERR_UNSUPPORTED
     assert swa(ws_bytes=0) == kb.ERR_WORKSPACE
     assert swa(B=0) == kb.OK
+    sbwd = lambda **kw: lib.kunlun_swa_bwd(vp(P), vp(P), vp(P), vp(kw.get("o", P)), vp(kw.get("lse", P)), vp(P),
+                                           vp(kw.get("dq", P)), vp(P), vp(P), vp(P), kw.get("B", 2), 2,
+                                           kw.get("d", 128), 100, 150, 255, 0, 0.1, 0, vp(kw.get("ws", P)), 1 << 20, None)
+    assert sbwd(lse=None) == kb.ERR_NULL
+    assert sbwd(o=None) == kb.ERR_NULL
+    assert sbwd(dq=None) == kb.ERR_NULL
+    assert sbwd(d=20) == kb.ERR_UNSUPPORTED
+    assert sbwd(ws=None) == kb.ERR_WORKSPACE
+    assert sbwd(B=0) == kb.OK
     bwd = lambda **kw: lib.kunlun_gdpa_bwd(vp(P), vp(P), vp(P), vp(kw.get("o", P)), vp(kw.get("lse", P)),
                                            vp(kw.get("d_o", P)), vp(kw.get("dq", P)), vp(P), vp(P), None, vp(P), 2, 2,
                                            64, 8, 64, kw.get("total_q", 16), 100, 0.1, kw.get("act", 3), None, 0,

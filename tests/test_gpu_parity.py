@@ -186,6 +186,28 @@ def test_swa_window_covering_sequence_equals_full_attention(kb):
     np.testing.assert_array_equal(a, b)
 
 
+def check_swa_bwd(kb, oracle, wl, window):
+    dt = wl.dtype
+    q, k, v, d_o = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt), to_dev(wl.d_o, dt)
+    off = offsets_dev(wl.kv_offsets)
+    ml = max(wl.max_kv, 1)
+    o, lse = kb.swa_fwd(q, k, v, off, window[0], window[1], wl.scale, max_len=ml)
+    dq, dk, dv = kb.swa_bwd(q, k, v, o, lse, d_o, off, window[0], window[1], wl.scale, max_len=ml)
+    torch.cuda.synchronize()
+    ref = oracle.swa_bwd(wl.q, wl.k, wl.v, wl.d_o, wl.kv_offsets, window[0], window[1], wl.scale)
+    for got, r, name in zip((dq, dk, dv), ref, ("dQ", "dK", "dV")):
+        assert_close(to_np(got), r, TOL[dt], f"swa bwd {name} window={window}")
+
+
+@pytest.mark.parametrize("window", [(255, 0), (3, 3), (0, 0), (40, 7), (-1, 0), (-1, -1)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 32)])
+def test_swa_backward(kb, oracle, window, dtype, d):
+    lens = [1, 0, 63, 64, 65, 130, 300, 2, 33]
+    sigma = 0.5 if dtype == "bf16" else 1.0
+    wl = W.make("cfg3", 4, B=len(lens), H=2, d=d, dtype=dtype, sigma=sigma, lengths=("list", lens))
+    check_swa_bwd(kb, oracle, wl, window)
+
+
 # ---------------- config 4: large jagged GDPA forward, sampled against the oracle ----------------
 
 def device_normal(shape, sigma, seed):
