@@ -150,14 +150,29 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     const int vr = (4 * g + ((lane & 15) >> 2)) * SM::V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
     // Q^T fragments (B operand): column = query 32*qb + r, contraction = channels 16*kc + 8g..
+    // The workgroup's query tile is fetched with whole-row coalesced loads (rows past the tile
+    // read as zero), staged in LDS in the K-tile row layout, and each wave picks its fragments.
+    constexpr int QT = QW * NW;
+    constexpr int Q_LOADS = QT * CT::CHUNKS / (64 * NW);
+    static_assert(QT * SM::K_STRIDE <= SM::TOTAL, "query tile must fit the tile buffers");
     bf16x8 qf[NQB][KC];
+    {
+        const char* qbase = (const char*)(Q + q_row0 * hd + (int64_t)h * D);
+        const __amdgpu_buffer_rsrc_t qrsrc =
+            __builtin_amdgcn_make_buffer_rsrc((void*)qbase, 0, (nq_wg - 1) * (int)row_bytes + D * 2, 0x00020000);
+        u32x4 qst[Q_LOADS];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        int qi = q_lo_w + 32 * qb + r;
-        qi = qi < nq_wg ? qi : nq_wg - 1;
-        const bf16_t* qrow = Q + (q_row0 + qi) * hd + (int64_t)h * D + 8 * g;
+        for (int i = 0; i < Q_LOADS; ++i)
+            qst[i] = __builtin_amdgcn_raw_buffer_load_b128(qrsrc, ct.goff, i * CT::ROWS_PER_LOAD * row_bytes, 0);
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) qf[qb][kc] = *(const bf16x8*)(qrow + 16 * kc);
+        for (int i = 0; i < Q_LOADS; ++i) *(u32x4*)(lds + ct.kw + i * CT::ROWS_PER_LOAD * SM::K_STRIDE) = qst[i];
+        if (NW > 1) __syncthreads();
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc)
+                qf[qb][kc] = *(const bf16x8*)(lds + (q_lo_w + 32 * qb) * SM::K_STRIDE + kr + 32 * kc);
+        if (NW > 1) __syncthreads();  // the tile buffers are reused for K/V from here on
     }
 
     // visible keys of this lane's query: key_lo .. key_lo + key_span (an empty range for padding
@@ -314,9 +329,12 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         }
     }
 
-    // ---- epilogue: lane holds query 32*qb + r, channels 32*db + 8*(v/4) + 4g + (v%4)
+    // ---- epilogue: lane holds query 32*qb + r, channels 32*db + 8*(v/4) + 4g + (v%4).  The wave
+    // transposes its O tile through LDS (its own region of the now idle tile buffers) and
+    // writes whole rows, 16 bytes per lane.
+    if (NW > 1) __syncthreads();  // every wave is done with the K/V tiles
     if (!wave_active) return;
-    bf16_t* O = (bf16_t*)p.o;
+    char* stage = lds + wave * (QW * SM::K_STRIDE);
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
         const int qi = 32 * qb + r;  // inside this wave's block
@@ -328,17 +346,25 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
                 p.lse[(int64_t)h * p.total_q + q_row0 + q_lo_w + qi] =
                     l_tot > 0.f ? (m_ref[qb] + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
         }
-        if (qi < nq) {
-            bf16_t* orow = O + (q_row0 + q_lo_w + qi) * hd + (int64_t)h * D + 4 * g;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    bf16x4 out;
+            for (int vg = 0; vg < 4; ++vg) {
+                bf16x4 out;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) out[e] = (bf16_t)(oacc[db][qb][4 * vg + e] * inv);
-                    *(bf16x4*)(orow + 32 * db + 8 * vg) = out;
-                }
+                for (int e = 0; e < 4; ++e) out[e] = (bf16_t)(oacc[db][qb][4 * vg + e] * inv);
+                *(bf16x4*)(stage + qi * SM::K_STRIDE + (32 * db + 8 * vg + 4 * g) * 2) = out;
+            }
+    }
+    {
+        bf16_t* obase = (bf16_t*)p.o + (q_row0 + q_lo_w) * hd + (int64_t)h * D;
+        constexpr int O_STORES = QW * CT::CHUNKS / 64;
+        const int chunk = lane % CT::CHUNKS, rsub = lane / CT::CHUNKS;
+#pragma unroll
+        for (int i = 0; i < O_STORES; ++i) {
+            const int row = i * (64 / CT::CHUNKS) + rsub;
+            const u32x4 val = *(const u32x4*)(stage + row * SM::K_STRIDE + chunk * 16);
+            if (row < nq) *(u32x4*)(obase + row * hd + chunk * 8) = val;
         }
     }
 }
