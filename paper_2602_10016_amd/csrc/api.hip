@@ -101,7 +101,9 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
     if (mfma_fwd_supported(p, dtype)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
         const int64_t wgs = (int64_t)B * H * ((max_q + 63) / 64);
-        if (schedule_is_moot(wgs, 4)) {  // every forward kernel fits 4 workgroups per compute unit
+        if (mfma_fwd_is_qtiled(p)) {
+            p.order = order;  // holds the query-tile prefix sums
+        } else if (schedule_is_moot(wgs, 4)) {  // every forward kernel fits 4 workgroups per compute unit
             p.order = nullptr;
         } else {
             p.order = order;

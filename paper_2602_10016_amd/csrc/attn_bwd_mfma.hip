@@ -70,8 +70,6 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
     char* ldsV = wbase + SM::TILE_BYTES;
     char* ldsP = wbase + 2 * SM::TILE_BYTES;
     char* ldsDS = ldsP + SM::P_BYTES;
-    auto uoff = [](int row, int byte) { return L::u_offset(row, byte); };
-    auto poff = [](int row, int byte) { return p_offset(row, byte); };
 
     // ---- prologue: Q and dO of the item into LDS; rows past nq are zero (they then add
     // nothing to dK, dV, and their dQ rows are never stored)
@@ -123,40 +121,87 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
 
     const int n_tiles = (n_kv + KT - 1) / KT;
     const float sc = SOFTMAX ? p.scale * LOG2E_B : p.scale;
-    u32x4 kst[L::LOADS], vst[L::LOADS];
-    if (wave < n_tiles) {
-        load_tile_regs<D>(kst, Kg + (int64_t)wave * KT * hd, hd, n_kv - wave * KT, lane);
-        load_tile_regs<D>(vst, Vg + (int64_t)wave * KT * hd, hd, n_kv - wave * KT, lane);
+    const uint32_t row_bytes = (uint32_t)(hd * 2);
+    const int64_t tile_bytes = (int64_t)KT * row_bytes;
+
+    // ---- everything that depends only on the lane, computed once per item (LDS byte offsets;
+    // "A"/"B" = the two transposing reads of one 8-element fragment)
+    const int s16 = lane & 15, hi16 = (lane >> 4) & 1;
+    const int chunk = lane % L::CHUNKS, rsub = lane / L::CHUNKS;
+    const uint32_t goff = (uint32_t)rsub * row_bytes + chunk * 16;  // this lane's chunk in a global tile
+    int uw[L::LOADS];   // the same chunk in a swizzled LDS tile, per load
+#pragma unroll
+    for (int i = 0; i < L::LOADS; ++i) uw[i] = L::u_offset(i * L::ROWS_PER_LOAD + rsub, chunk * 16);
+    int rr[KC];         // row fragment (row r, channels 16*kc + 8g ..); rows r + 32*qb add a constant
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) rr[kc] = L::u_offset(r, (2 * kc + g) * 16);
+    int ktA[DB], ktB[DB], qtA[DB], qtB[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        const int colb = (32 * db + 16 * hi16 + 4 * (s16 & 3)) * 2;
+        ktA[db] = L::u_offset(4 * g + (s16 >> 2), colb);          // K^T: keys 16c + 4g + 0..3 (+ 16c rows)
+        ktB[db] = L::u_offset(8 + 4 * g + (s16 >> 2), colb);      //      keys 16c + 8 + 4g + 0..3
+        qtA[db] = L::u_offset(8 * g + (s16 >> 2), colb);          // Q^T, dO^T: queries 16j + 8g + 0..3
+        qtB[db] = L::u_offset(8 * g + 4 + (s16 >> 2), colb);      //            queries 16j + 8g + 4..7
     }
-    for (int kt = wave; kt < n_tiles; kt += NW) {
-        store_u_tile<D>(ldsK, kst, lane);
-        store_u_tile<D>(ldsV, vst, lane);
-        if (kt + NW < n_tiles) {
-            const int nt = kt + NW;
-            load_tile_regs<D>(kst, Kg + (int64_t)nt * KT * hd, hd, n_kv - nt * KT, lane);
-            load_tile_regs<D>(vst, Vg + (int64_t)nt * KT * hd, hd, n_kv - nt * KT, lane);
+    const int ptA = p_offset(8 * g + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);  // P, dS: like Q^T
+    const int ptB = p_offset(8 * g + 4 + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);
+    int pw[4];          // P / dS writes: query r (+ 32*qb rows), keys 8*vg + 4g ..
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) pw[vg] = p_offset(r, (8 * vg + 4 * g) * 2);
+    // dK^T / dV^T staging: padded rows (2D + 16 bytes) over the dead K and V tiles
+    constexpr int ST_STRIDE = 2 * D + 16;
+    static_assert(KT * ST_STRIDE <= 2 * SM::TILE_BYTES, "staging must fit the K and V tiles");
+    const int st_w = r * ST_STRIDE + 8 * g;
+    const int st_r = rsub * ST_STRIDE + chunk * 16;
+    auto tr_read = [](const char* a, const char* b) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, b));
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // K/V tile loads: buffer resource over the valid rows of the tile (rows past the end of the
+    // history read as zero), non-temporal
+    auto fetch = [&](u32x4 (&ks)[L::LOADS], u32x4 (&vs)[L::LOADS], int kt) {
+        const int rows = (n_kv - kt * KT) < KT ? (n_kv - kt * KT) : KT;
+        const int bytes = (rows - 1) * (int)row_bytes + D * 2;
+        const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Kg + kt * tile_bytes), 0, bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Vg + kt * tile_bytes), 0, bytes, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < L::LOADS; ++i) {
+            ks[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, goff, i * L::ROWS_PER_LOAD * row_bytes, 2);
+            vs[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, goff, i * L::ROWS_PER_LOAD * row_bytes, 2);
         }
+    };
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    u32x4 kst[L::LOADS], vst[L::LOADS];
+    if (wave < n_tiles) fetch(kst, vst, wave);
+    for (int kt = wave; kt < n_tiles; kt += NW) {
+#pragma unroll
+        for (int i = 0; i < L::LOADS; ++i) {
+            *(u32x4*)(ldsK + uw[i]) = kst[i];
+            *(u32x4*)(ldsV + uw[i]) = vst[i];
+        }
+        if (kt + NW < n_tiles) fetch(kst, vst, kt + NW);
         // ---- S^T = K Q^T and dP^T = V dO^T
         f32x16 sacc[NQB], dpacc[NQB];
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) { sacc[qb][v] = 0.f; dpacc[qb][v] = 0.f; }
-#pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const bf16x8 ka = read_u_frag<D>(ldsK, kc, r, g);
-            const bf16x8 va = read_u_frag<D>(ldsV, kc, r, g);
+            const bf16x8 ka = *(const bf16x8*)(ldsK + rr[kc]);
+            const bf16x8 va = *(const bf16x8*)(ldsV + rr[kc]);
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb) {
-                const bf16x8 qf = read_u_frag<D>(ldsQ, kc, 32 * qb + r, g);
-                const bf16x8 df = read_u_frag<D>(ldsDO, kc, 32 * qb + r, g);
-                sacc[qb] = mfma32(ka, qf, sacc[qb]);
-                dpacc[qb] = mfma32(va, df, dpacc[qb]);
+                const bf16x8 qf = *(const bf16x8*)(ldsQ + qb * 32 * L::ROW_BYTES + rr[kc]);
+                const bf16x8 df = *(const bf16x8*)(ldsDO + qb * 32 * L::ROW_BYTES + rr[kc]);
+                sacc[qb] = mfma32(ka, qf, kc == 0 ? zero16 : sacc[qb]);
+                dpacc[qb] = mfma32(va, df, kc == 0 ? zero16 : dpacc[qb]);
             }
         }
         // ---- P^T, dS^T in registers; bf16 copies to the P / dS tiles ([query][key])
         const int key_base = kt * KT;
         const bool need_mask = key_base + KT > n_kv;
+        const unsigned keys_left = (unsigned)(n_kv - key_base - 4 * g);  // key 8*(v/4) + (v%4) + 4g < n_kv - key_base
         bf16x8 dsf[NQB][2];
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
@@ -177,7 +222,7 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
             if (need_mask) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const bool ok = key_base + c_row(v, g) < n_kv;
+                    const bool ok = (unsigned)(8 * (v >> 2) + (v & 3)) < keys_left;
                     pv[v] = ok ? pv[v] : 0.f;
                     dsv[v] = ok ? dsv[v] : 0.f;
                 }
@@ -192,9 +237,8 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
                 bf16x4 pk, dk4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { pk[e] = (bf16_t)pv[4 * vg + e]; dk4[e] = (bf16_t)dsv[4 * vg + e]; }
-                const int off = p_offset(32 * qb + r, (8 * vg + 4 * g) * 2);
-                *(bf16x4*)(ldsP + off) = pk;
-                *(bf16x4*)(ldsDS + off) = dk4;
+                *(bf16x4*)(ldsP + qb * 32 * 64 + pw[vg]) = pk;
+                *(bf16x4*)(ldsDS + qb * 32 * 64 + pw[vg]) = dk4;
             }
         }
         // ---- dQ^T += K^T dS^T  (keys in the register order of the C layout)
@@ -202,7 +246,7 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
         for (int db = 0; db < DB; ++db) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                const bf16x8 a = read_tr_frag(ldsK, uoff, 16 * c + 4 * g, 16 * c + 8 + 4 * g, 32 * db, lane);
+                const bf16x8 a = tr_read(ldsK + c * 16 * L::ROW_BYTES + ktA[db], ldsK + c * 16 * L::ROW_BYTES + ktB[db]);
 #pragma unroll
                 for (int qb = 0; qb < NQB; ++qb) dqacc[db][qb] = mfma32(a, dsf[qb][c], dqacc[db][qb]);
             }
@@ -211,24 +255,22 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
         bf16x8 pb[QCH], dsb[QCH];
 #pragma unroll
         for (int j = 0; j < QCH; ++j) {
-            pb[j] = read_tr_frag(ldsP, poff, 16 * j + 8 * g, 16 * j + 8 * g + 4, 0, lane);
-            dsb[j] = read_tr_frag(ldsDS, poff, 16 * j + 8 * g, 16 * j + 8 * g + 4, 0, lane);
+            pb[j] = tr_read(ldsP + j * 16 * 64 + ptA, ldsP + j * 16 * 64 + ptB);
+            dsb[j] = tr_read(ldsDS + j * 16 * 64 + ptA, ldsDS + j * 16 * 64 + ptB);
         }
-        const int rows_valid = n_kv - key_base;
+        const int rows = (n_kv - key_base) < KT ? (n_kv - key_base) : KT;
+        const int out_bytes = (rows - 1) * (int)row_bytes + D * 2;
+        char* stage = ldsK;  // K and V tiles are dead from here on
 #pragma unroll
         for (int which = 0; which < 2; ++which) {
-            // which = 0: dV into the (now dead) V tile; which = 1: dK into the K tile
-            char* stage = which == 0 ? ldsV : ldsK;
             const char* src = which == 0 ? ldsDO : ldsQ;
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 f32x16 acc;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-#pragma unroll
                 for (int j = 0; j < QCH; ++j) {
-                    const bf16x8 a = read_tr_frag(src, uoff, 16 * j + 8 * g, 16 * j + 8 * g + 4, 32 * db, lane);
-                    acc = mfma32(a, which == 0 ? pb[j] : dsb[j], acc);
+                    const bf16x8 a = tr_read(src + j * 16 * L::ROW_BYTES + qtA[db], src + j * 16 * L::ROW_BYTES + qtB[db]);
+                    acc = mfma32(a, which == 0 ? pb[j] : dsb[j], j == 0 ? zero16 : acc);
                 }
                 // lane: key r, channels 32*db + 8*vg + 4g + 0..3
 #pragma unroll
@@ -236,16 +278,16 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
                     bf16x4 out;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) out[e] = (bf16_t)acc[4 * vg + e];
-                    *(bf16x4*)(stage + L::k_offset(r, 4 * db + vg) + 8 * g) = out;
+                    *(bf16x4*)(stage + st_w + (32 * db + 8 * vg) * 2) = out;
                 }
             }
-            bf16_t* dst = (which == 0 ? DVg : DKg) + (int64_t)key_base * hd;
-            const int chunk = lane % L::CHUNKS, rsub = lane / L::CHUNKS;
+            // whole rows out, 16 bytes per lane; the buffer resource drops rows past the history
+            char* dst = (char*)(which == 0 ? DVg : DKg) + key_base * (int64_t)row_bytes;
+            const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc((void*)dst, 0, out_bytes, 0x00020000);
 #pragma unroll
             for (int i = 0; i < L::LOADS; ++i) {
-                const int row = i * L::ROWS_PER_LOAD + rsub;
-                const u32x4 val = *(const u32x4*)(stage + L::k_offset(row, chunk));
-                if (row < rows_valid) __builtin_nontemporal_store(val, (u32x4*)(dst + row * hd + chunk * 8));
+                const u32x4 val = *(const u32x4*)(stage + st_r + i * L::ROWS_PER_LOAD * ST_STRIDE);
+                __builtin_amdgcn_raw_buffer_store_b128(val, orsrc, goff, i * L::ROWS_PER_LOAD * row_bytes, 2);
             }
         }
     }

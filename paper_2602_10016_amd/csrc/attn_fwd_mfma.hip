@@ -414,12 +414,14 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
     attn_fwd_dispatch<D, NQB, NW, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
 }
 
-// Sliding-window self-attention: grid = H * (query tiles of all sequences), cut into 8
+// Query-tiled launch, for sliding-window self-attention and for GDPA with long query
+// sequences (the PFFN direction: the sequence tokens are the queries, a few context tokens per
+// example are keys and values): grid = H * (query tiles of all examples), cut into 8
 // contiguous ranges, one per XCD (workgroup i runs on XCD i % 8), so that the query tiles of
-// one (sequence, head) - which share most of their keys - meet in the same L2.
-// tile_start[b] = number of query tiles before sequence b (written by the prefix kernel).
-template <int D, int NQB, int NW, int OCC>
-__global__ __launch_bounds__(64 * NW, OCC) void swa_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
+// one (example, head) - which share their keys - meet in the same L2.
+// tile_start[b] = number of query tiles before example b (written by the prefix kernel).
+template <int D, int NQB, int NW, int OCC, bool WINDOWED>
+__global__ __launch_bounds__(64 * NW, OCC) void qtile_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
     __shared__ __attribute__((aligned(1024))) char lds[FwdSmem<D>::TOTAL];
     constexpr int QT = 32 * NQB * NW;
     const int64_t n_items = (int64_t)tile_start[p.B] * p.H;
@@ -429,7 +431,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void swa_fwd_mfma_kernel(AttnParams p
     if (slot >= per_xcd) return;
     const int64_t item = xcd * per_xcd + slot;
     if (item >= n_items) return;
-    // items ordered by sequence, then head, then query tile
+    // items ordered by example, then head, then query tile
     int lo = 0, hi = p.B - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -442,20 +444,24 @@ __global__ __launch_bounds__(64 * NW, OCC) void swa_fwd_mfma_kernel(AttnParams p
     const int qt = (int)(rem % nt);
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
+    const int64_t q0 = q_begin(p, b);
+    const int64_t nq_all = q_end(p, b) - q0;
     const int64_t q_first = (int64_t)qt * QT;
-    const int nq = (int)((n_kv - q_first) < QT ? (n_kv - q_first) : QT);
-    attn_fwd_dispatch<D, NQB, NW, true>(p, lds, KUNLUN_ACT_SOFTMAX, h, k0 + q_first, nq, q_first, k0, n_kv);
+    const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
+    attn_fwd_dispatch<D, NQB, NW, WINDOWED>(p, lds, p.head_act[h], h, q0 + q_first, nq, q_first, k0, n_kv);
 }
 
-// Exclusive prefix sum of ceil(len_b / tile) over the sequences, single workgroup.
-__global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int B, int tile,
-                                                           int32_t* __restrict__ tile_start) {
+// Exclusive prefix sum of ceil(len_b / tile) over the examples, single workgroup.  off == null:
+// every example has `dense_len` rows.
+__global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int dense_len, int B,
+                                                           int tile, int32_t* __restrict__ tile_start) {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
     const int per = (B + 1023) / 1024;
     const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
+    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + tile - 1) / tile; };
     int sum = 0;
-    for (int b = b0; b < b1; ++b) sum += (off[b + 1] - off[b] + tile - 1) / tile;
+    for (int b = b0; b < b1; ++b) sum += tiles_of(b);
     part[tid] = sum;
     __syncthreads();
     for (int o = 1; o < 1024; o <<= 1) {
@@ -467,7 +473,7 @@ __global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __rest
     int run = part[tid] - sum;
     for (int b = b0; b < b1; ++b) {
         tile_start[b] = run;
-        run += (off[b + 1] - off[b] + tile - 1) / tile;
+        run += tiles_of(b);
     }
     if (tid == 1023) tile_start[B] = part[1023];
 }
@@ -490,23 +496,29 @@ static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int D, int NQB, int NW, int OCC>
-static hipError_t launch_swa(const AttnParams& p, hipStream_t stream) {
-    // self-attention: an upper bound of the query-tile count sizes the grid
+template <int D, int NQB, int NW, int OCC, bool WINDOWED>
+static hipError_t launch_qtiled(const AttnParams& p, hipStream_t stream) {
+    // an upper bound of the query-tile count sizes the grid
     constexpr int QT = 32 * NQB * NW;
     const int64_t max_tiles = p.total_q / QT + p.B;
     const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
     const unsigned grid = (unsigned)(per_xcd * 8);
     int32_t* tile_start = const_cast<int32_t*>(p.order);
-    hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.kv_off, p.B, QT, tile_start);
-    hipLaunchKernelGGL((swa_fwd_mfma_kernel<D, NQB, NW, OCC>), dim3(grid), dim3(64 * NW), 0, stream, p, tile_start);
+    hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, QT, tile_start);
+    hipLaunchKernelGGL((qtile_fwd_mfma_kernel<D, NQB, NW, OCC, WINDOWED>), dim3(grid), dim3(64 * NW), 0, stream, p,
+                       tile_start);
     return hipGetLastError();
 }
 
+bool mfma_fwd_is_qtiled(const AttnParams& p) { return p.windowed || p.max_q > 64; }
+
 hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
-    // 32 queries per wave, up to 255 registers per wave, two waves per SIMD.
-    // sliding window: 128-query tiles (4 waves) - fewer K/V tile loads per query than 64
-    if (p.windowed) return p.d == 128 ? launch_swa<128, 1, 4, 2>(p, stream) : launch_swa<64, 1, 4, 2>(p, stream);
+    // 32 queries per wave, up to 255 registers per wave, two or three waves per SIMD.
+    // Query-tiled launches use 128-query tiles (4 waves): fewer K/V tile loads per query.
+    if (p.windowed)
+        return p.d == 128 ? launch_qtiled<128, 1, 4, 2, true>(p, stream) : launch_qtiled<64, 1, 4, 2, true>(p, stream);
+    if (p.max_q > 64)
+        return p.d == 128 ? launch_qtiled<128, 1, 4, 2, false>(p, stream) : launch_qtiled<64, 1, 4, 2, false>(p, stream);
     if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
     return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
 }

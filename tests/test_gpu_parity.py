@@ -108,6 +108,29 @@ def test_jagged_queries(kb, oracle):
         check_gdpa_fwd(kb, oracle, wl, act)
 
 
+@pytest.mark.parametrize("d", [64, 128])
+def test_long_jagged_queries_few_keys(kb, oracle, d):
+    """The PFFN direction of Eq. (GDPA): the sequence tokens are the queries, a few context
+    tokens per example are keys and values (query-tiled launch)."""
+    rng = np.random.default_rng(11)
+    B, H = 10, 3
+    lens_q = np.array([700, 1, 0, 128, 129, 255, 256, 257, 64, 400])
+    lens_kv = np.array([16, 32, 8, 0, 64, 33, 1, 48, 64, 20])
+    wl = W.make("cfg2", 12, B=B, H=H, d=d, Nq=1, lengths=("list", lens_kv), scale=0.5 / math.sqrt(d))
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = int(lens_q.max())
+    check_gdpa_fwd(kb, oracle, wl, 3)
+    check_gdpa_fwd(kb, oracle, wl, 0, head_act=[0, 5, 3])
+
+
+def test_dense_long_queries(kb, oracle):
+    wl = W.make("cfg2", 13, B=5, H=2, d=128, Nq=300, lengths=("list", [40, 0, 64, 7, 100]), scale=0.5 / math.sqrt(128))
+    check_gdpa_fwd(kb, oracle, wl, 3)
+    check_gdpa_fwd(kb, oracle, wl, 0)
+
+
 def test_fp32_generic_path_jagged(kb, oracle):
     wl = W.make("cfg1", 6, B=9, H=3, d=40, Nq=5, lengths=("list", [0, 1, 63, 64, 65, 129, 300, 2, 77]),
                 scale=1 / math.sqrt(40))
