@@ -321,6 +321,47 @@ def test_backward_per_head_activations(kb, oracle):
     check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
 
 
+# ---------------- HIP graph capture ----------------
+
+def test_graph_capture_replays_match_eager(kb):
+    """The calls enqueue kernels only (no allocation, no memset, no synchronisation), so a captured
+    graph of forward + backward + window replays bit-identically to the eager calls."""
+    wl = W.make("cfg5", 21, B=40, H=8, d=128, Nq=64, lengths=("uniform", 1, 300))
+    ws3 = W.make("cfg3", 22, B=6)
+    dt = "bf16"
+    q, k, v, d_o = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt), to_dev(wl.d_o, dt)
+    kvo = offsets_dev(wl.kv_offsets)
+    qs, ks, vs, so = to_dev(ws3.q, dt), to_dev(ws3.k, dt), to_dev(ws3.v, dt), offsets_dev(ws3.kv_offsets)
+    mk = wl.max_kv
+    wsz = max(kb.workspace_bytes(op, 64, 8, 128, 2048, 2048, q.shape[0], k.shape[0]) for op in range(4))
+    w1, w2, w3 = (torch.empty(wsz, dtype=torch.uint8, device="cuda") for _ in range(3))
+    o, lse = torch.empty_like(q), torch.empty((8, q.shape[0]), dtype=torch.float32, device="cuda")
+    o_s = torch.empty_like(qs)
+
+    def run():
+        kb.gdpa_fwd(q, k, v, kvo, 0.05, 0, max_q=64, max_kv=mk, out=o, lse=lse, workspace=w1)
+        g = kb.gdpa_bwd(q, k, v, d_o, kvo, 0.05, 0, o=o, lse=lse, max_q=64, max_kv=mk, workspace=w2)
+        kb.swa_fwd(qs, ks, vs, so, 255, 0, ws3.scale, max_len=ws3.max_kv, out=o_s, want_lse=False, workspace=w3)
+        return g
+
+    eager = [t.clone() for t in run()] + [o.clone(), o_s.clone()]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = run()
+    for rep in range(3):
+        o.zero_(); o_s.zero_()
+        for t in captured:
+            t.zero_()
+        junk = torch.randn(1 << 20, device="cuda").sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(list(captured) + [o, o_s], eager):
+            assert torch.equal(got, ref), f"replay {rep} differs from the eager result"
+        del junk
+
+
 # ---------------- degenerate calls ----------------
 
 def test_empty_batch_and_all_empty_histories(kb):
