@@ -11,22 +11,8 @@ from .build import build
 
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
 
-_lib = ctypes.CDLL(build())
 _dp = ctypes.POINTER(ctypes.c_double)
 _ip = ctypes.POINTER(ctypes.c_int32)
-_lib.oracle_gdpa_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                 ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_int, _ip]
-_lib.oracle_gdpa_bwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, _dp, _ip, _ip, ctypes.c_int, ctypes.c_int,
-                                 ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
-                                 ctypes.c_int, _ip]
-_lib.oracle_swa_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
-_lib.oracle_swa_bwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
-_lib.oracle_act_value.argtypes = [ctypes.c_int, ctypes.c_double]
-_lib.oracle_act_value.restype = ctypes.c_double
-_lib.oracle_act_deriv.argtypes = [ctypes.c_int, ctypes.c_double]
-_lib.oracle_act_deriv.restype = ctypes.c_double
 
 
 def _f64(a):
@@ -46,83 +32,109 @@ def _check(q, k, v, H, d):
     assert q.shape[1:] == (H, d) and k.shape[1:] == (H, d) and v.shape == k.shape
 
 
-def gdpa_fwd(q, k, v, kv_offsets, scale, act, q_offsets=None, max_q=None, head_act=None):
-    """Returns (O, LSE).  q_offsets=None: dense queries, max_q rows per example."""
-    q, k, v = _f64(q), _f64(k), _f64(v)
-    H, d = q.shape[1], q.shape[2]
-    _check(q, k, v, H, d)
-    kvo, qo, ha = _i32(kv_offsets), _i32(q_offsets), _i32(head_act)
-    B = kvo.size - 1
-    if qo is None:
-        assert max_q is not None and q.shape[0] == B * max_q
-    else:
-        assert qo.size == B + 1 and qo[-1] == q.shape[0]
-        max_q = 0
-    assert kvo[-1] == k.shape[0]
-    o = np.empty_like(q)
-    lse = np.empty((H, q.shape[0]), dtype=np.float64)
-    rc = _lib.oracle_gdpa_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _p(qo, _ip), _p(kvo, _ip), B, H, d, int(max_q),
-                              q.shape[0], float(scale), int(act), _p(ha, _ip))
-    if rc != 0:
-        raise ValueError("oracle_gdpa_fwd: unknown activation")
-    return o, lse
+class OracleLib:
+    """One loaded build of kunlun_oracle.c.  The module-level functions below use the default
+    build; tests that plant mistakes in a copy of the C source load that copy through this class."""
+
+    def __init__(self, path):
+        lib = ctypes.CDLL(path)
+        lib.oracle_gdpa_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                        ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_int, _ip]
+        lib.oracle_gdpa_bwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, _dp, _ip, _ip, ctypes.c_int, ctypes.c_int,
+                                        ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_double,
+                                        ctypes.c_int, _ip]
+        lib.oracle_swa_fwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+        lib.oracle_swa_bwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+        lib.oracle_act_value.argtypes = [ctypes.c_int, ctypes.c_double]
+        lib.oracle_act_value.restype = ctypes.c_double
+        lib.oracle_act_deriv.argtypes = [ctypes.c_int, ctypes.c_double]
+        lib.oracle_act_deriv.restype = ctypes.c_double
+        self._lib = lib
+
+    def gdpa_fwd(self, q, k, v, kv_offsets, scale, act, q_offsets=None, max_q=None, head_act=None):
+        """Returns (O, LSE).  q_offsets=None: dense queries, max_q rows per example."""
+        q, k, v = _f64(q), _f64(k), _f64(v)
+        H, d = q.shape[1], q.shape[2]
+        _check(q, k, v, H, d)
+        kvo, qo, ha = _i32(kv_offsets), _i32(q_offsets), _i32(head_act)
+        B = kvo.size - 1
+        if qo is None:
+            assert max_q is not None and q.shape[0] == B * max_q
+        else:
+            assert qo.size == B + 1 and qo[-1] == q.shape[0]
+            max_q = 0
+        assert kvo[-1] == k.shape[0]
+        o = np.empty_like(q)
+        lse = np.empty((H, q.shape[0]), dtype=np.float64)
+        rc = self._lib.oracle_gdpa_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _p(qo, _ip), _p(kvo, _ip), B, H, d,
+                                       int(max_q), q.shape[0], float(scale), int(act), _p(ha, _ip))
+        if rc != 0:
+            raise ValueError("oracle_gdpa_fwd: unknown activation")
+        return o, lse
+
+    def gdpa_bwd(self, q, k, v, d_o, kv_offsets, scale, act, q_offsets=None, max_q=None, head_act=None):
+        """Returns (dQ, dK, dV), the gradient of <O, dO>."""
+        q, k, v, d_o = _f64(q), _f64(k), _f64(v), _f64(d_o)
+        H, d = q.shape[1], q.shape[2]
+        _check(q, k, v, H, d)
+        assert d_o.shape == q.shape
+        kvo, qo, ha = _i32(kv_offsets), _i32(q_offsets), _i32(head_act)
+        B = kvo.size - 1
+        if qo is None:
+            assert max_q is not None and q.shape[0] == B * max_q
+        else:
+            assert qo.size == B + 1 and qo[-1] == q.shape[0]
+            max_q = 0
+        assert kvo[-1] == k.shape[0]
+        dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+        rc = self._lib.oracle_gdpa_bwd(_p(q), _p(k), _p(v), _p(d_o), _p(dq), _p(dk), _p(dv), _p(qo, _ip),
+                                       _p(kvo, _ip), B, H, d, int(max_q), q.shape[0], k.shape[0], float(scale),
+                                       int(act), _p(ha, _ip))
+        if rc != 0:
+            raise ValueError("oracle_gdpa_bwd: unknown activation")
+        return dq, dk, dv
+
+    def swa_fwd(self, q, k, v, offsets, left, right, scale):
+        """Sliding-window softmax self-attention; left/right < 0 means unbounded.  Returns (O, LSE)."""
+        q, k, v = _f64(q), _f64(k), _f64(v)
+        H, d = q.shape[1], q.shape[2]
+        _check(q, k, v, H, d)
+        off = _i32(offsets)
+        assert off[-1] == q.shape[0] == k.shape[0]
+        o = np.empty_like(q)
+        lse = np.empty((H, q.shape[0]), dtype=np.float64)
+        self._lib.oracle_swa_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _p(off, _ip), off.size - 1, H, d, q.shape[0],
+                                 int(left), int(right), float(scale))
+        return o, lse
+
+    def swa_bwd(self, q, k, v, d_o, offsets, left, right, scale):
+        q, k, v, d_o = _f64(q), _f64(k), _f64(v), _f64(d_o)
+        H, d = q.shape[1], q.shape[2]
+        _check(q, k, v, H, d)
+        off = _i32(offsets)
+        assert off[-1] == q.shape[0] == k.shape[0]
+        dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+        self._lib.oracle_swa_bwd(_p(q), _p(k), _p(v), _p(d_o), _p(dq), _p(dk), _p(dv), _p(off, _ip), off.size - 1, H,
+                                 d, q.shape[0], int(left), int(right), float(scale))
+        return dq, dk, dv
+
+    def act_value(self, act, x):
+        return self._lib.oracle_act_value(int(act), float(x))
+
+    def act_deriv(self, act, x):
+        return self._lib.oracle_act_deriv(int(act), float(x))
+
+    def num_threads(self):
+        return int(self._lib.oracle_num_threads())
 
 
-def gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, q_offsets=None, max_q=None, head_act=None):
-    """Returns (dQ, dK, dV), the gradient of <O, dO>."""
-    q, k, v, d_o = _f64(q), _f64(k), _f64(v), _f64(d_o)
-    H, d = q.shape[1], q.shape[2]
-    _check(q, k, v, H, d)
-    assert d_o.shape == q.shape
-    kvo, qo, ha = _i32(kv_offsets), _i32(q_offsets), _i32(head_act)
-    B = kvo.size - 1
-    if qo is None:
-        assert max_q is not None and q.shape[0] == B * max_q
-    else:
-        assert qo.size == B + 1 and qo[-1] == q.shape[0]
-        max_q = 0
-    assert kvo[-1] == k.shape[0]
-    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
-    rc = _lib.oracle_gdpa_bwd(_p(q), _p(k), _p(v), _p(d_o), _p(dq), _p(dk), _p(dv), _p(qo, _ip), _p(kvo, _ip), B, H,
-                              d, int(max_q), q.shape[0], k.shape[0], float(scale), int(act), _p(ha, _ip))
-    if rc != 0:
-        raise ValueError("oracle_gdpa_bwd: unknown activation")
-    return dq, dk, dv
-
-
-def swa_fwd(q, k, v, offsets, left, right, scale):
-    """Sliding-window softmax self-attention; left/right < 0 means unbounded.  Returns (O, LSE)."""
-    q, k, v = _f64(q), _f64(k), _f64(v)
-    H, d = q.shape[1], q.shape[2]
-    _check(q, k, v, H, d)
-    off = _i32(offsets)
-    assert off[-1] == q.shape[0] == k.shape[0]
-    o = np.empty_like(q)
-    lse = np.empty((H, q.shape[0]), dtype=np.float64)
-    _lib.oracle_swa_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _p(off, _ip), off.size - 1, H, d, q.shape[0],
-                        int(left), int(right), float(scale))
-    return o, lse
-
-
-def swa_bwd(q, k, v, d_o, offsets, left, right, scale):
-    q, k, v, d_o = _f64(q), _f64(k), _f64(v), _f64(d_o)
-    H, d = q.shape[1], q.shape[2]
-    _check(q, k, v, H, d)
-    off = _i32(offsets)
-    assert off[-1] == q.shape[0] == k.shape[0]
-    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
-    _lib.oracle_swa_bwd(_p(q), _p(k), _p(v), _p(d_o), _p(dq), _p(dk), _p(dv), _p(off, _ip), off.size - 1, H, d,
-                        q.shape[0], int(left), int(right), float(scale))
-    return dq, dk, dv
-
-
-def act_value(act, x):
-    return _lib.oracle_act_value(int(act), float(x))
-
-
-def act_deriv(act, x):
-    return _lib.oracle_act_deriv(int(act), float(x))
-
-
-def num_threads():
-    return int(_lib.oracle_num_threads())
+_default = OracleLib(build())
+gdpa_fwd = _default.gdpa_fwd
+gdpa_bwd = _default.gdpa_bwd
+swa_fwd = _default.swa_fwd
+swa_bwd = _default.swa_bwd
+act_value = _default.act_value
+act_deriv = _default.act_deriv
+num_threads = _default.num_threads
