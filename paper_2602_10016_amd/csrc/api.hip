@@ -47,10 +47,10 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
     switch (op) {
     case KUNLUN_OP_GDPA_FWD:
     case KUNLUN_OP_SWA_FWD:
-    case KUNLUN_OP_SWA_BWD:
         return WS_HEADER_BYTES + order_bytes(B);
     case KUNLUN_OP_GDPA_BWD:
-        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_workspace_tail(B, H, d, max_q, total_q);
+    case KUNLUN_OP_SWA_BWD:
+        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_tiled_workspace(B, H, total_q);
     default:
         return 0;
     }
@@ -160,6 +160,8 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
             if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
         }
         e = launch_mfma_bwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
+    } else if (mfma_bwd_tiled_supported(p, dtype)) {
+        e = launch_mfma_bwd_tiled(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), any_softmax, s);
     } else {
         e = launch_scalar_bwd(p, dtype, s);
     }
@@ -227,9 +229,11 @@ int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, c
     p.windowed = 1;
     p.left = window_left < 0 ? -1 : window_left;
     p.right = window_right < 0 ? -1 : window_right;
-    // one wavefront per gradient row (generic kernels): dQ rows over their windows, then dK/dV
-    // rows over the queries that see them
-    const hipError_t e = launch_scalar_bwd(p, dtype, (hipStream_t)stream);
+    hipError_t e;
+    if (mfma_bwd_tiled_supported(p, dtype))
+        e = launch_mfma_bwd_tiled(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), true, (hipStream_t)stream);
+    else  // one wavefront per gradient row: dQ rows over their windows, then dK/dV rows
+        e = launch_scalar_bwd(p, dtype, (hipStream_t)stream);
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 

@@ -222,13 +222,18 @@ def check_swa_bwd(kb, oracle, wl, window):
         assert_close(to_np(got), r, TOL[dt], f"swa bwd {name} window={window}")
 
 
-@pytest.mark.parametrize("window", [(255, 0), (3, 3), (0, 0), (40, 7), (-1, 0), (-1, -1)])
+@pytest.mark.parametrize("window", [(255, 0), (3, 3), (0, 0), (40, 7), (-1, 0), (-1, -1), (127, 128), (0, 200)])
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 32)])
 def test_swa_backward(kb, oracle, window, dtype, d):
-    lens = [1, 0, 63, 64, 65, 130, 300, 2, 33]
+    lens = [1, 0, 63, 64, 65, 130, 300, 2, 33, 513]
     sigma = 0.5 if dtype == "bf16" else 1.0
     wl = W.make("cfg3", 4, B=len(lens), H=2, d=d, dtype=dtype, sigma=sigma, lengths=("list", lens))
     check_swa_bwd(kb, oracle, wl, window)
+
+
+def test_cfg3_sliding_window_backward(kb, oracle):
+    wl = W.make("cfg3", 0, B=32)
+    check_swa_bwd(kb, oracle, wl, wl.window)
 
 
 # ---------------- config 4: large jagged GDPA forward, sampled against the oracle ----------------
@@ -314,6 +319,29 @@ def test_backward_ragged(kb, oracle, d, Nq):
     wl = W.make("cfg5", 2, B=len(RAGGED), H=2, d=d, Nq=Nq, lengths=("list", RAGGED), scale=0.5 / math.sqrt(d))
     for act in (3, 0):
         check_gdpa_bwd(kb, oracle, wl, act)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("act", list(ACTS))
+def test_backward_long_jagged_queries_few_keys(kb, oracle, d, act):
+    """Backward in the PFFN direction (sequence tokens are the queries): two-pass matrix-core path."""
+    rng = np.random.default_rng(31)
+    H = 2
+    lens_q = np.array([300, 1, 0, 128, 129, 65, 257, 90])
+    lens_kv = np.array([16, 32, 8, 0, 64, 33, 1, 100])
+    B = len(lens_q)
+    wl = W.make("cfg5", 32, B=B, H=H, d=d, Nq=1, lengths=("list", lens_kv), scale=0.5 / math.sqrt(d))
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.d_o = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32))
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = int(lens_q.max())
+    check_gdpa_bwd(kb, oracle, wl, ACTS[act])
+
+
+def test_backward_dense_long_queries_per_head(kb, oracle):
+    wl = W.make("cfg5", 33, B=4, H=6, d=128, Nq=150, lengths=("list", [40, 0, 64, 7]), scale=0.5 / math.sqrt(128))
+    check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
 
 
 def test_backward_per_head_activations(kb, oracle):
