@@ -180,7 +180,9 @@ def main():
         q2, k2, v2, do2 = dev(w2.q), dev(w2.k), dev(w2.v), dev(w2.d_o)
         off2 = torch.from_numpy(w2.kv_offsets).cuda()
         o2 = torch.empty_like(q2)
-        wsx = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+        need = max(kb.workspace_bytes(kb.OP_GDPA_BWD, w2.B, w2.H, w2.d, w2.Nq, 1024, w2.total_q, w2.total_kv),
+                   kb.workspace_bytes(kb.OP_SWA_FWD, 128, 4, 128, 2048, 2048, 1 << 20, 1 << 20))
+        wsx = torch.empty(need, dtype=torch.uint8, device="cuda")
         ms = timed(lambda: kb.gdpa_fwd(q2, k2, v2, off2, w2.scale, act, max_q=w2.Nq, max_kv=1024, out=o2, want_lse=False, workspace=wsx))
         by, fl = W.gdpa_bytes(w2.H, w2.d, w2.total_q, w2.total_kv), W.gdpa_flops(w2.H, w2.d, w2.Nq, w2.total_kv)
         other["cfg2_gdpa_fwd"] = {"us": round(ms * 1e3, 1), "gbps": round(by / ms / 1e6, 1), "tflops": round(fl / ms / 1e9, 1)}

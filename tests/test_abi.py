@@ -101,3 +101,10 @@ def test_swa_and_bwd_reject_bad_arguments(kb):
     assert bwd(act=3, lse=None, o=None, ws=None) == kb.ERR_WORKSPACE  # no softmax head: o, lse optional
     assert bwd(total_q=17) == kb.ERR_SHAPE
     assert bwd(ws=None) == kb.ERR_WORKSPACE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr

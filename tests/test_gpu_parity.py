@@ -406,3 +406,8 @@ def test_empty_batch_and_all_empty_histories(kb):
         assert torch.all(o == 0)
         if act == 0:
             assert torch.all(torch.isneginf(lse))
+
+
+def test_smoke_entry_point():
+    import __graft_entry__
+    __graft_entry__.smoke()
