@@ -152,7 +152,7 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
     hipError_t e;
     if (mfma_bwd_supported(p, dtype)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
-        if (schedule_is_moot((int64_t)B * H, d == 128 ? 1 : 4)) {  // d=128: one 128 KB workgroup per compute unit
+        if (schedule_is_moot((int64_t)B * H, d == 128 ? (max_q > 32 ? 2 : 1) : 4)) {  // workgroups of the kernel per compute unit
             p.order = nullptr;
         } else {
             p.order = order;

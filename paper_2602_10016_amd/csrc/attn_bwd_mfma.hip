@@ -393,7 +393,7 @@ static hipError_t launch_bwd(const AttnParams& p, hipStream_t stream) {
 
 hipError_t launch_mfma_bwd(const AttnParams& p, void*, hipStream_t stream) {
     const bool one_block = p.max_q <= 32;
-    if (p.d == 128) return one_block ? launch_bwd<128, 1, 4>(p, stream) : launch_bwd<128, 2, 4>(p, stream);
+    if (p.d == 128) return one_block ? launch_bwd<128, 1, 4>(p, stream) : launch_mfma_bwd_pair(p, stream);
     return one_block ? launch_bwd<64, 1, 2>(p, stream) : launch_bwd<64, 2, 2>(p, stream);
 }
 

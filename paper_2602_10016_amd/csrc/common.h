@@ -50,6 +50,8 @@ bool mfma_fwd_is_qtiled(const AttnParams& p);
 bool mfma_bwd_supported(const AttnParams& p, int dtype);
 hipError_t launch_mfma_bwd(const AttnParams& p, void* workspace_tail, hipStream_t stream);
 size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
+// d = 128 with 33..64 queries per example: wave pairs share each key tile (two workgroups per compute unit).
+hipError_t launch_mfma_bwd_pair(const AttnParams& p, hipStream_t stream);
 // Two-pass matrix-core backward (sliding window, or more than 64 queries per example).
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype);
 size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q);
