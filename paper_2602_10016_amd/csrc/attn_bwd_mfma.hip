@@ -105,7 +105,7 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
             } else {
                 lse2[qb] = INFINITY;  // weight exp2(s - inf) = 0
             }
-            delta[qb] += __shfl_xor(delta[qb], 32, 64);
+            delta[qb] = halves_sum(delta[qb]);
         }
     }
     if (NW > 1) __syncthreads();

@@ -100,7 +100,7 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
             }
             delta = acc;
         }
-        delta += __shfl_xor(delta, 32, 64);
+        delta = halves_sum(delta);
     }
     __syncthreads();
 

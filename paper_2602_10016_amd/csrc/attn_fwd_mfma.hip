@@ -18,11 +18,9 @@
 //     O^T += V^T P^T           (MFMA; V^T via transposing LDS reads)
 // Softmax keeps a running maximum and sum per query (one query per lane column) and rescales
 // O^T when the maximum grows; the activation path has no such stage.
-#include "mfma_tile.h"
+#include "attn_fwd_score.h"
 
 namespace kunlun {
-
-constexpr float LOG2E = 1.4426950408889634f;
 
 // LDS tiles of the forward kernels: 32 rows, row-major, each row padded so that every access
 // pattern is free of bank conflicts and every offset is affine in (row, column):
@@ -87,12 +85,6 @@ struct CoopTile {
         for (int i = 0; i < LOADS; ++i) *(u32x4*)(ldsV + vw + i * ROWS_PER_LOAD * SM::V_STRIDE) = vs[i];
     }
 };
-
-// Largest growth of a row maximum (log2 units) that is tolerated before the running
-// reference of the online softmax is moved: weights stay below 2^8, and the accumulators are
-// rescaled only when some query of the wave exceeds it.  The result is unchanged in exact
-// arithmetic because numerator and denominator use the same reference.
-constexpr float SOFTMAX_LAZY_LOG2 = 8.f;
 
 // One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's
 // tile; t0_wg: position of that first query inside its sequence (sliding window only).
@@ -242,58 +234,8 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         bf16x8 pf[NQB][2];
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
-            float pv[16];  // raw scores, then weights
-#pragma unroll
-            for (int v = 0; v < 16; ++v) pv[v] = sacc[qb][v];
-            // key k of this lane's query is visible iff (unsigned)(k - key_lo) <= key_span
             const unsigned rel0 = (unsigned)(key_base + 4 * g - key_lo[qb]);
-            if (SOFTMAX) {
-                if (need_mask) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span[qb];
-                        pv[v] = ok ? pv[v] : -INFINITY;
-                    }
-                }
-                // scale > 0 (checked on the host), so the maximum commutes with the scaling;
-                // scores are handled in log2 units (scale * log2 e folded into sc)
-                float mx = pv[0];
-#pragma unroll
-                for (int v = 1; v < 16; ++v) mx = fmaxf(mx, pv[v]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * sc;  // the other lane half holds the other 16 keys
-                const bool grow = mx > m_ref[qb] + SOFTMAX_LAZY_LOG2;
-                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                    const float corr = grow ? fast_exp2(m_ref[qb] - mx) : 1.f;
-                    m_ref[qb] = grow ? mx : m_ref[qb];
-                    l_run[qb] *= corr;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= corr;
-                }
-                const float neg_m = m_ref[qb] == -INFINITY ? 0.f : -m_ref[qb];
-                float sum = 0.f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    pv[v] = fast_exp2(fmaf(pv[v], sc, neg_m));
-                    sum += pv[v];
-                }
-                l_run[qb] += sum;
-            } else if (need_mask) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span[qb];
-                    const float w = act_fast<ACT>(pv[v] * sc);
-                    pv[v] = ok ? w : 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) pv[v] = act_fast<ACT>(pv[v] * sc);
-            }
-#pragma unroll
-            for (int c = 0; c < 2; ++c)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[qb][c][e] = (bf16_t)pv[8 * c + e];
+            score_to_weights<ACT, DB, NQB>(sacc[qb], need_mask, rel0, key_span[qb], sc, m_ref[qb], l_run[qb], oacc, qb, pf[qb]);
         }
         // ---- O^T += V^T P^T
 #pragma unroll
@@ -340,7 +282,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         const int qi = 32 * qb + r;  // inside this wave's block
         float inv = 1.f;
         if (SOFTMAX) {
-            const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+            const float l_tot = halves_sum(l_run[qb]);
             inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             if (p.lse && g == 0 && qi < nq)
                 p.lse[(int64_t)h * p.total_q + q_row0 + q_lo_w + qi] =
@@ -414,70 +356,6 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
     attn_fwd_dispatch<D, NQB, NW, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
 }
 
-// Query-tiled launch, for sliding-window self-attention and for GDPA with long query
-// sequences (the PFFN direction: the sequence tokens are the queries, a few context tokens per
-// example are keys and values): grid = H * (query tiles of all examples), cut into 8
-// contiguous ranges, one per XCD (workgroup i runs on XCD i % 8), so that the query tiles of
-// one (example, head) - which share their keys - meet in the same L2.
-// tile_start[b] = number of query tiles before example b (written by the prefix kernel).
-template <int D, int NQB, int NW, int OCC, bool WINDOWED>
-__global__ __launch_bounds__(64 * NW, OCC) void qtile_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start) {
-    __shared__ __attribute__((aligned(1024))) char lds[FwdSmem<D>::TOTAL];
-    constexpr int QT = 32 * NQB * NW;
-    const int64_t n_items = (int64_t)tile_start[p.B] * p.H;
-    const int64_t per_xcd = (n_items + 7) / 8;
-    const int xcd = blockIdx.x & 7;
-    const int64_t slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return;
-    const int64_t item = xcd * per_xcd + slot;
-    if (item >= n_items) return;
-    // items ordered by example, then head, then query tile
-    int lo = 0, hi = p.B - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if ((int64_t)tile_start[mid] * p.H <= item) lo = mid; else hi = mid - 1;
-    }
-    const int b = lo;
-    const int nt = tile_start[b + 1] - tile_start[b];
-    const int64_t rem = item - (int64_t)tile_start[b] * p.H;
-    const int h = (int)(rem / nt);
-    const int qt = (int)(rem % nt);
-    const int64_t k0 = p.kv_off[b];
-    const int n_kv = p.kv_off[b + 1] - (int)k0;
-    const int64_t q0 = q_begin(p, b);
-    const int64_t nq_all = q_end(p, b) - q0;
-    const int64_t q_first = (int64_t)qt * QT;
-    const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
-    attn_fwd_dispatch<D, NQB, NW, WINDOWED>(p, lds, p.head_act[h], h, q0 + q_first, nq, q_first, k0, n_kv);
-}
-
-// Exclusive prefix sum of ceil(len_b / tile) over the examples, single workgroup.  off == null:
-// every example has `dense_len` rows.
-__global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int dense_len, int B,
-                                                           int tile, int32_t* __restrict__ tile_start) {
-    __shared__ int part[1024];
-    const int tid = threadIdx.x;
-    const int per = (B + 1023) / 1024;
-    const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
-    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + tile - 1) / tile; };
-    int sum = 0;
-    for (int b = b0; b < b1; ++b) sum += tiles_of(b);
-    part[tid] = sum;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        const int v = tid >= o ? part[tid - o] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - sum;
-    for (int b = b0; b < b1; ++b) {
-        tile_start[b] = run;
-        run += tiles_of(b);
-    }
-    if (tid == 1023) tile_start[B] = part[1023];
-}
-
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
     if (dtype != KUNLUN_BF16 || (p.d != 64 && p.d != 128)) return false;
     // the online softmax takes the row maximum before scaling: it needs scale > 0
@@ -496,29 +374,12 @@ static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int D, int NQB, int NW, int OCC, bool WINDOWED>
-static hipError_t launch_qtiled(const AttnParams& p, hipStream_t stream) {
-    // an upper bound of the query-tile count sizes the grid
-    constexpr int QT = 32 * NQB * NW;
-    const int64_t max_tiles = p.total_q / QT + p.B;
-    const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
-    const unsigned grid = (unsigned)(per_xcd * 8);
-    int32_t* tile_start = const_cast<int32_t*>(p.order);
-    hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, QT, tile_start);
-    hipLaunchKernelGGL((qtile_fwd_mfma_kernel<D, NQB, NW, OCC, WINDOWED>), dim3(grid), dim3(64 * NW), 0, stream, p,
-                       tile_start);
-    return hipGetLastError();
-}
-
 bool mfma_fwd_is_qtiled(const AttnParams& p) { return p.windowed || p.max_q > 64; }
 
-hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
+hipError_t launch_mfma_fwd(const AttnParams& p, void* workspace_tail, hipStream_t stream) {
     // 32 queries per wave, up to 255 registers per wave, two or three waves per SIMD.
     // Query-tiled launches use 128-query tiles (4 waves): fewer K/V tile loads per query.
-    if (p.windowed)
-        return p.d == 128 ? launch_qtiled<128, 1, 4, 2, true>(p, stream) : launch_qtiled<64, 1, 4, 2, true>(p, stream);
-    if (p.max_q > 64)
-        return p.d == 128 ? launch_qtiled<128, 1, 4, 2, false>(p, stream) : launch_qtiled<64, 1, 4, 2, false>(p, stream);
+    if (mfma_fwd_is_qtiled(p)) return launch_mfma_fwd_qtiled(p, workspace_tail, stream);
     if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
     return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
 }

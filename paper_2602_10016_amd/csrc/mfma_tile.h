@@ -169,6 +169,19 @@ __device__ __forceinline__ bf16x8 read_tr_frag(const char* lds, OFFSET offset, i
     return __builtin_bit_cast(bf16x8, both);
 }
 
+// Value of x in the lane 32 further (or 32 back), paired with the lane's own: the gfx950
+// half-wave swap is a VALU operation, where a shuffle would take an LDS round trip.
+// Returns both values in an order that depends on the lane half; use for symmetric reductions.
+__device__ __forceinline__ void both_halves(float x, float& a, float& b) {
+    unsigned u = __builtin_bit_cast(unsigned, x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // r[0] = {low half, low half}, r[1] = {high, high}
+    unsigned r0 = r[0], r1 = r[1];
+    a = __builtin_bit_cast(float, r0);
+    b = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float halves_max(float x) { float a, b; both_halves(x, a, b); return fmaxf(a, b); }
+__device__ __forceinline__ float halves_sum(float x) { float a, b; both_halves(x, a, b); return a + b; }
+
 // Key index (inside a 32-key tile) of register v of the score C layout for lane half g.
 __device__ __forceinline__ int c_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v & 3); }
 
