@@ -344,6 +344,23 @@ def test_backward_dense_long_queries_per_head(kb, oracle):
     check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
 
 
+def test_backward_d128_jagged_queries_up_to_64_all_activations(kb, oracle):
+    """d = 128 with up to 64 queries per example (the wave-pair kernel): query counts 0..64 in one
+    batch, histories with 0, 1 and 2 pairs' worth of tiles and ragged tails, one activation per head."""
+    rng = np.random.default_rng(41)
+    H, d = 6, 128
+    lens_q = np.array([64, 33, 0, 1, 32, 63, 48, 64, 17, 40, 64, 5])
+    lens_kv = np.array([0, 1, 31, 32, 33, 63, 64, 65, 96, 97, 129, 200])
+    B = len(lens_q)
+    wl = W.make("cfg5", 41, B=B, H=H, d=d, Nq=1, lengths=("list", lens_kv), scale=0.5 / math.sqrt(d))
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.d_o = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32))
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = 64
+    check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
+
+
 def test_backward_per_head_activations(kb, oracle):
     wl = W.make("cfg5", 3, B=10, H=6, lengths=("uniform", 8, 96), scale=0.125)
     check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
