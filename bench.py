@@ -217,6 +217,30 @@ def main():
         other["cfg3_swa_fwd"] = entry(*t, W.swa_bytes(w3.H, w3.d, w3.total_kv),
                                       W.swa_flops(w3.H, w3.d, W.swa_pairs(w3.lengths, *w3.window)))
 
+        # The rows built beyond the three calls of the step: sliding-window backward on the cfg3 batch
+        # and the PFFN direction of GDPA (the cfg3 sequences are the queries, 32 context tokens per
+        # example are keys and values), forward and backward.
+        do3 = dev(np.random.default_rng(args.seed + 5).standard_normal(w3.q.shape, dtype=np.float32))
+        ws3 = torch.empty(kb.workspace_bytes(kb.OP_SWA_BWD, w3.B, w3.H, w3.d, 2048, 2048, w3.total_kv, w3.total_kv),
+                          dtype=torch.uint8, device="cuda")
+        o3f, lse3 = kb.swa_fwd(q3, k3, v3, off3, w3.window[0], w3.window[1], w3.scale, max_len=2048, workspace=ws3)
+        t = timed(lambda: kb.swa_bwd(q3, k3, v3, o3f, lse3, do3, off3, w3.window[0], w3.window[1], w3.scale, max_len=2048, workspace=ws3), n=10)
+        other["cfg3_swa_bwd"] = entry(*t, 2 * W.swa_bytes(w3.H, w3.d, w3.total_kv),
+                                      2.5 * W.swa_flops(w3.H, w3.d, W.swa_pairs(w3.lengths, *w3.window)))
+        n_ctx = 32
+        kc3 = device_normal(torch, (w3.B * n_ctx, w3.H, w3.d), 0.5, 31)
+        vc3 = device_normal(torch, (w3.B * n_ctx, w3.H, w3.d), 0.5, 32)
+        offc = torch.arange(0, (w3.B + 1) * n_ctx, n_ctx, dtype=torch.int32, device="cuda")
+        wsp = torch.empty(kb.workspace_bytes(kb.OP_GDPA_BWD, w3.B, w3.H, w3.d, 2048, n_ctx, w3.total_kv, w3.B * n_ctx),
+                          dtype=torch.uint8, device="cuda")
+        elt = w3.H * w3.d * 2
+        t = timed(lambda: kb.gdpa_fwd(q3, kc3, vc3, offc, 1.0 / n_ctx, act, q_offsets=off3, max_q=2048, max_kv=n_ctx, out=o3, want_lse=False, workspace=wsp), n=10)
+        other["pffn_direction_gdpa_fwd"] = entry(*t, 2 * w3.total_kv * elt + 2 * w3.B * n_ctx * elt,
+                                                 4.0 * w3.d * w3.H * n_ctx * w3.total_kv)
+        t = timed(lambda: kb.gdpa_bwd(q3, kc3, vc3, do3, offc, 1.0 / n_ctx, act, q_offsets=off3, max_q=2048, max_kv=n_ctx, workspace=wsp), n=10)
+        other["pffn_direction_gdpa_bwd"] = entry(*t, 3 * w3.total_kv * elt + 4 * w3.B * n_ctx * elt,
+                                                 10.0 * w3.d * w3.H * n_ctx * w3.total_kv)
+
         # Diagnostic, not a workload of the paper: the same forward entry point on a shape that IS
         # matrix-core-bound (512 queries per example: 512 flop per K/V byte, above the ridge), to show
         # what the MFMA pipeline of these kernels sustains when HBM is out of the way.
