@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "common.h"
+#include "tile_map.h"
 
 using namespace kunlun;
 
@@ -47,10 +48,10 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
     switch (op) {
     case KUNLUN_OP_GDPA_FWD:
     case KUNLUN_OP_SWA_FWD:
-        return WS_HEADER_BYTES + order_bytes(B) + mfma_fwd_qtiled_workspace(B, total_q);
+        return WS_HEADER_BYTES + tile_table_bytes(B, total_q);
     case KUNLUN_OP_GDPA_BWD:
     case KUNLUN_OP_SWA_BWD:
-        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_tiled_workspace(B, H, total_q);
+        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_tiled_workspace(B, H, total_q, total_kv);
     default:
         return 0;
     }
@@ -110,7 +111,7 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
             e = launch_schedule(kv_offsets, B, max_kv, order, s);
             if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
         }
-        e = launch_mfma_fwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
+        e = launch_mfma_fwd(p, s);
     } else {
         e = launch_scalar_fwd(p, dtype, s);
     }
@@ -196,7 +197,7 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
     hipError_t e;
     if (mfma_fwd_supported(p, dtype)) {
         p.order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);  // holds the query-tile prefix sums
-        e = launch_mfma_fwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
+        e = launch_mfma_fwd(p, s);
     } else {
         e = launch_scalar_fwd(p, dtype, s);
     }

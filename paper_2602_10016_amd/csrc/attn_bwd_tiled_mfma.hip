@@ -3,21 +3,24 @@
 // more than 64 queries per example (the PFFN direction of Eq. (GDPA): sequence tokens are the
 // queries).  Scores are recomputed tile by tile in both passes; nothing of score size is stored.
 //
-//   pass A (dQ):     one workgroup per (example, head, 128-query tile), the mirror image of the
+//   pass A (dQ):     one workgroup per (example, 128-query tile, head), the mirror image of the
 //                    forward kernel: each wave owns 32 queries (Q^T and dO^T fragments in
 //                    registers) and the waves stream the K/V tiles of the tile's key range;
 //                        S^T = K Q^T,  dP^T = V dO^T,  dS^T in registers,  dQ^T += K^T dS^T.
-//   pass B (dK, dV): one workgroup per (example, head, 128-key tile): each wave owns 32 keys
+//   pass B (dK, dV): one workgroup per (example, 128-key tile, head): each wave owns 32 keys
 //                    (K^T and V^T fragments in registers) and the waves stream the Q/dO tiles of
 //                    the queries that see those keys;
 //                        S = Q K^T,  dP = dO V^T,  P and dS in registers (one key per lane),
 //                        dV^T += dO^T P,  dK^T += Q^T dS.
 // In both passes the score tile comes out of the first contraction with the owned dimension
 // on the lanes, so the packed registers are directly the B operand of the second contraction
-// and the streamed operand is read transposed from LDS (ds_read_b64_tr_b16).
+// and the streamed operand is read transposed from LDS (ds_read_b64_tr_b16).  Streamed tiles
+// travel by buffer-load-to-LDS into a ring of three stages (lds_ring.h); a tile that is read
+// both as row fragments and transposed sits in LDS once, in the two-way swizzle.
 // Softmax heads use the forward LSE and delta = rowsum(dO * O), computed once by a small
-// kernel into the workspace.
-#include "mfma_tile.h"
+// kernel into the workspace; pass B streams both per query tile next to Q and dO.
+#include "lds_ring.h"
+#include "tile_map.h"
 
 namespace kunlun {
 
@@ -32,62 +35,6 @@ struct PadTiles {
     static constexpr int ROW_TILE = KT * ROW_STRIDE;
     static constexpr int TR_TILE = KT * TR_STRIDE;
 };
-
-// Cooperative loads of a 32-row tile of a [tokens, H, D] tensor by 64*NW threads (whole rows
-// coalesce); rows past `rows_valid` read as zero through the buffer resource.
-template <int D, int NW>
-struct TileIO {
-    using PT = PadTiles<D>;
-    static constexpr int CHUNKS = D / 8;
-    static constexpr int SLOTS = KT * CHUNKS;
-    static constexpr int LOADS = SLOTS / (64 * NW);
-    static constexpr int ROWS_PER_LOAD = 64 * NW / CHUNKS;
-    static_assert(LOADS >= 1 && SLOTS % (64 * NW) == 0, "tile does not split evenly over the workgroup");
-    uint32_t goff, row_bytes;
-    int w_row, w_tr;
-
-    __device__ __forceinline__ void init(int tid, uint32_t row_stride_bytes) {
-        const int row0 = tid / CHUNKS, chunk = tid % CHUNKS;
-        row_bytes = row_stride_bytes;
-        goff = (uint32_t)row0 * row_stride_bytes + chunk * 16;
-        w_row = row0 * PT::ROW_STRIDE + chunk * 16;
-        w_tr = row0 * PT::TR_STRIDE + chunk * 16;
-    }
-    __device__ __forceinline__ void load(u32x4 (&st)[LOADS], const char* __restrict__ tile_base, int rows_valid) const {
-        const int rows = rows_valid < KT ? rows_valid : KT;
-        const int bytes = (rows - 1) * (int)row_bytes + D * 2;
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tile_base, 0, bytes, 0x00020000);
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) st[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff, i * ROWS_PER_LOAD * row_bytes, 0);
-    }
-    __device__ __forceinline__ void store_row(char* lds, const u32x4 (&st)[LOADS]) const {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) *(u32x4*)(lds + w_row + i * ROWS_PER_LOAD * PT::ROW_STRIDE) = st[i];
-    }
-    __device__ __forceinline__ void store_tr(char* lds, const u32x4 (&st)[LOADS]) const {
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i) *(u32x4*)(lds + w_tr + i * ROWS_PER_LOAD * PT::TR_STRIDE) = st[i];
-    }
-};
-
-// Stage a tile of up to 32*NW rows (global rows row0.., head h) into LDS in the row layout
-// (whole-row coalesced loads, zero rows past n_rows).  Caller synchronises.
-template <int D, int NW>
-__device__ __forceinline__ void stage_rows(char* lds, const bf16_t* tensor, int64_t row0, int n_rows, int h, int H,
-                                           const TileIO<D, NW>& io) {
-    using PT = PadTiles<D>;
-    using IO = TileIO<D, NW>;
-    constexpr int N_LOADS = 32 * NW * IO::CHUNKS / (64 * NW);
-    const char* base = (const char*)(tensor + (row0 * H + h) * D);
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (n_rows - 1) * (int)io.row_bytes + D * 2, 0x00020000);
-    u32x4 st[N_LOADS];
-#pragma unroll
-    for (int i = 0; i < N_LOADS; ++i)
-        st[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, io.goff, i * IO::ROWS_PER_LOAD * io.row_bytes, 0);
-#pragma unroll
-    for (int i = 0; i < N_LOADS; ++i) *(u32x4*)(lds + io.w_row + i * IO::ROWS_PER_LOAD * PT::ROW_STRIDE) = st[i];
-}
 
 // A wave's 32 x D fp32 result tile in the C layout (lane: column r = row of the output tensor,
 // registers: channels 32*db + 8*(v/4) + 4g + v%4) -> bf16 rows of a [tokens, H, D] tensor,
@@ -116,43 +63,68 @@ __device__ __forceinline__ void store_tile_rows(char* stage, const f32x16 (&acc)
     }
 }
 
-// The transposed fragment (A operand) of channel block db for the 16 tile rows that the C
-// layout puts in registers 8c .. 8c+7 (rows 16c + 4g + 0..3 and 16c + 8 + 4g + 0..3).
-template <int D>
-__device__ __forceinline__ bf16x8 tr_frag(const char* tile, int vr, int db, int c) {
-    using PT = PadTiles<D>;
-    const char* src = tile + vr + 64 * db + c * 16 * PT::TR_STRIDE;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * PT::TR_STRIDE));
+// One 8-element fragment from two transposing reads (rows .. +3 at a, rows .. +3 at b).
+__device__ __forceinline__ bf16x8 tr_pair(const char* a, const char* b) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, b));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-// ------------------------------------------------------------------ pass A: dQ
-
-template <int D>
-struct DqSmem {
+// LDS of both passes: a ring of three stages; the prologue stages the workgroup's own 128 rows
+// (4 tiles, K-tile swizzle) in the end of the ring, and the epilogue transposes the results
+// through padded rows.
+template <int D, int STAGE_EXTRA>
+struct TiledSmem {
     using PT = PadTiles<D>;
-    static constexpr int BUF = 2 * PT::ROW_TILE + PT::TR_TILE;  // K rows | K for transposed reads | V rows
-    static constexpr int TOTAL = 2 * BUF;
+    static constexpr int TILE = KT * D * 2;
+    static constexpr int STAGE = 2 * TILE + STAGE_EXTRA;
+    static constexpr int TOTAL = 3 * STAGE;
+    static constexpr int OWN_BYTES = 4 * TILE;
+    static_assert(TOTAL - OWN_BYTES >= STAGE, "the staged rows must leave the first stage free");
+    static_assert(4 * PT::ROW_TILE <= TOTAL, "output staging must fit");
 };
+
+// Per-lane LDS read offsets inside a tile in the two-way swizzle.
+template <int D>
+struct UFrag {
+    int row0, trA, trB;
+    __device__ __forceinline__ void init(int lane) {
+        using L = TileLayout<D>;
+        const int r = lane & 31, g = lane >> 5, s16 = lane & 15, hi16 = (lane >> 4) & 1;
+        const int colb = (16 * hi16 + 4 * (s16 & 3)) * 2;
+        row0 = L::u_offset(r, g * 16);                      // row fragment: row r, channels 16*kc + 8g ..: row0 ^ (kc << 5)
+        trA = L::u_offset(4 * g + (s16 >> 2), colb);         // transposed: rows 16c + 4g + 0..3, channel block db: trA ^ (db << 6)
+        trB = L::u_offset(8 + 4 * g + (s16 >> 2), colb);     //             rows 16c + 8 + 4g + 0..3
+    }
+    __device__ __forceinline__ bf16x8 row(const char* tile, int kc) const { return *(const bf16x8*)(tile + (row0 ^ (kc << 5))); }
+    // A operand (row = channel 32*db + lane%32) for the 16 tile rows that the C layout puts in registers 8c .. 8c+7
+    __device__ __forceinline__ bf16x8 transposed(const char* tile, int db, int c) const {
+        const char* base = tile + c * 16 * D * 2;
+        return tr_pair(base + (trA ^ (db << 6)), base + (trB ^ (db << 6)));
+    }
+};
+
+// ------------------------------------------------------------------ pass A: dQ
 
 template <int D, int NW, int ACT, bool WINDOWED>
 __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __restrict__ delta_ws, char* lds, int h,
                                             int64_t q_row0, int nq_wg, int64_t t0_wg, int64_t k0, int n_kv) {
     using PT = PadTiles<D>;
-    using IO = TileIO<D, NW>;
-    using SM = DqSmem<D>;
+    using L = TileLayout<D>;
+    using SM = TiledSmem<D, 0>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16, DB = D / 32;
-    static_assert(32 * NW * PT::ROW_STRIDE <= SM::TOTAL, "query tile must fit the tile buffers");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert(NW == 4, "four waves of 32 queries");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
     const uint32_t row_bytes = (uint32_t)(hd * 2);
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
     const char* K = (const char*)((const bf16_t*)p.k + (k0 * p.H + h) * D);
     const char* V = (const char*)((const bf16_t*)p.v + (k0 * p.H + h) * D);
+    const uint32_t lds0 = lds_address(lds);
 
     const int q_lo_w = wave * 32;
     int nq = nq_wg - q_lo_w;
@@ -175,23 +147,37 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __
         w_end = hi / KT + 1;
     }
 
-    IO io;
-    io.init(tid, row_bytes);
-    const int kr = r * PT::ROW_STRIDE + g * 16;
-    const int vr = (4 * g + ((lane & 15) >> 2)) * PT::TR_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    // stage = K tile (two-way swizzle: row fragments and transposed reads) | V tile (row fragments)
+    TileDma<D, NW, SWZ_U> kdma;
+    TileDma<D, NW, SWZ_K> vdma;
+    kdma.init(lane, wave, row_bytes);
+    vdma.init(lane, wave, row_bytes);
+    constexpr int LOADS_PER_TILE = 2 * TileDma<D, NW, SWZ_U>::IPW;
+    auto issue = [&](int kt, int stage) {
+        const uint32_t dst = lds0 + stage * SM::STAGE;
+        kdma.issue(K + kt * tile_bytes, n_kv - kt * KT, dst);
+        vdma.issue(V + kt * tile_bytes, n_kv - kt * KT, dst + SM::TILE);
+    };
+    const int n_steps = kt_end - kt_begin;
+    if (n_steps > 0) issue(kt_begin, 0);
 
-    // Q^T and dO^T fragments of this wave's queries (B operands), via LDS
+    // Q^T and dO^T fragments of this wave's queries (B operands), via the end of the ring
     bf16x8 qf[KC], dof[KC];
-    stage_rows<D, NW>(lds, (const bf16_t*)p.q, q_row0, nq_wg, h, p.H, io);
-    __syncthreads();
+    {
+        char* own = lds + SM::TOTAL - SM::OWN_BYTES;
+        const int64_t goff = q_row0 * hd + (int64_t)h * D;
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.q + goff), row_bytes, nq_wg, tid);
+        __syncthreads();
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(lds + q_lo_w * PT::ROW_STRIDE + kr + 32 * kc);
-    __syncthreads();
-    stage_rows<D, NW>(lds, (const bf16_t*)p.d_o, q_row0, nq_wg, h, p.H, io);
-    __syncthreads();
+        for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+        __syncthreads();
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.d_o + goff), row_bytes, nq_wg, tid);
+        __syncthreads();
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) dof[kc] = *(const bf16x8*)(lds + q_lo_w * PT::ROW_STRIDE + kr + 32 * kc);
-    __syncthreads();
+        for (int kc = 0; kc < KC; ++kc) dof[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+        __syncthreads();
+    }
+    if (n_steps > 1) issue(kt_begin + 1, 1);
 
     // this lane's query: softmax statistics and visible key range
     float lse2 = INFINITY, delta = 0.f;
@@ -220,51 +206,58 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __
 #pragma unroll
         for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
     const float sc = SOFTMAX ? p.scale * LOG2E_T : p.scale;
+    UFrag<D> uf;
+    uf.init(lane);
+    const int v_rd = L::k_offset(r, g);  // V row fragment: v_rd ^ (kc << 5)
 
-    u32x4 kst[IO::LOADS], vst[IO::LOADS];
-    auto fetch = [&](int kt) {
-        if (kt < kt_end) {
-            io.load(kst, K + kt * tile_bytes, n_kv - kt * KT);
-            io.load(vst, V + kt * tile_bytes, n_kv - kt * KT);
-        }
-    };
-    fetch(kt_begin);
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        char* ldsK = lds + ((kt - kt_begin) & 1) * SM::BUF;
-        char* ldsKt = ldsK + PT::ROW_TILE;
-        char* ldsV = ldsKt + PT::TR_TILE;
-        io.store_row(ldsK, kst);
-        io.store_tr(ldsKt, kst);
-        io.store_row(ldsV, vst);
-        __syncthreads();  // tile kt complete; every wave is done with the other buffer
-        fetch(kt + 1);
+    int stage = 0;
+    for (int i = 0; i < n_steps; ++i) {
+        // the loads above were issued before the lse / delta loads that the compiler tracks, so
+        // its own waits can only be stricter than needed
+        if (i + 1 < n_steps) wait_vmcnt<LOADS_PER_TILE>();
+        else wait_vmcnt<0>();
+        __syncthreads();  // tile i complete; every wave is done with the stage of tile i-1
+        if (i + 2 < n_steps) issue(kt_begin + i + 2, stage == 0 ? 2 : stage - 1);
+        const char* ldsK = lds + stage * SM::STAGE;
+        const char* ldsV = ldsK + SM::TILE;
+        stage = stage == 2 ? 0 : stage + 1;
+        const int kt = kt_begin + i;
         if (!wave_active || kt < w_begin || kt >= w_end) continue;
         f32x16 sacc, dpacc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const bf16x8 ka = *(const bf16x8*)(ldsK + kr + 32 * kc);
-            const bf16x8 va = *(const bf16x8*)(ldsV + kr + 32 * kc);
+            const bf16x8 ka = uf.row(ldsK, kc);
+            const bf16x8 va = *(const bf16x8*)(ldsV + (v_rd ^ (kc << 5)));
             sacc = mfma32(ka, qf[kc], sacc);
             dpacc = mfma32(va, dof[kc], dpacc);
         }
-        // dS^T in registers (lane: query, registers: keys of the tile)
-        const unsigned rel0 = (unsigned)(kt * KT + 4 * g - key_lo);
+        // dS^T in registers (lane: query, registers: keys of the tile).  Interior tiles - every
+        // (query, key) pair inside the history and the window - skip the visibility test.
+        const int key_base = kt * KT;
+        bool need_mask = key_base + KT > n_kv;
+        if (WINDOWED) {
+            const int tq_lo = t0, tq_hi = t0 + nq - 1;
+            if (p.left >= 0 && key_base < tq_hi - p.left) need_mask = true;
+            if (p.right >= 0 && key_base + KT - 1 > tq_lo + p.right) need_mask = true;
+        }
         float dsv[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const float s = sacc[v] * sc;
-            float ds;
             if (SOFTMAX) {
-                ds = fast_exp2(s - lse2) * (dpacc[v] - delta) * p.scale;
+                dsv[v] = fast_exp2(s - lse2) * (dpacc[v] - delta) * p.scale;
             } else {
                 float val, der;
                 act_fast_vd<ACT>(s, val, der);
-                ds = dpacc[v] * der * p.scale;
+                dsv[v] = dpacc[v] * der * p.scale;
             }
-            const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span;
-            dsv[v] = ok ? ds : 0.f;
+        }
+        if (need_mask) {
+            const unsigned rel0 = (unsigned)(key_base + 4 * g - key_lo);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dsv[v] = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span ? dsv[v] : 0.f;
         }
         bf16x8 dsf[2];
 #pragma unroll
@@ -275,9 +268,9 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int c = 0; c < 2; ++c) dqacc[db] = mfma32(tr_frag<D>(ldsKt, vr, db, c), dsf[c], dqacc[db]);
+            for (int c = 0; c < 2; ++c) dqacc[db] = mfma32(uf.transposed(ldsK, db, c), dsf[c], dqacc[db]);
     }
-    __syncthreads();  // every wave is done with the tile buffers
+    __syncthreads();  // every wave is done with the ring
     if (!wave_active) return;
     store_tile_rows<D>(lds + wave * PT::ROW_TILE, dqacc, (bf16_t*)p.dq + (q_row0 + q_lo_w) * hd + (int64_t)h * D, hd, nq,
                        lane);
@@ -285,30 +278,26 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __
 
 // ------------------------------------------------------------------ pass B: dK, dV
 
-template <int D>
-struct DkvSmem {
-    using PT = PadTiles<D>;
-    static constexpr int STATS = 256;  // lse (log2 units) and delta of the 32 queries of a tile
-    static constexpr int BUF = 2 * PT::ROW_TILE + 2 * PT::TR_TILE + STATS;  // Q rows | Q tr | dO rows | dO tr | stats
-    static constexpr int TOTAL = 2 * BUF;
-};
+constexpr int STATS_BYTES = 512;  // per stage: lse of 64 queries (32 used), then delta of 64 queries
 
 template <int D, int NW, int ACT, bool WINDOWED>
 __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* __restrict__ delta_ws, char* lds, int h,
                                               int64_t k_row0, int nk_wg, int kpos0_wg, int64_t q0, int nq_all) {
     using PT = PadTiles<D>;
-    using IO = TileIO<D, NW>;
-    using SM = DkvSmem<D>;
+    using L = TileLayout<D>;
+    using SM = TiledSmem<D, STATS_BYTES>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16, DB = D / 32;
-    static_assert(32 * NW * PT::ROW_STRIDE <= SM::TOTAL, "key tile must fit the tile buffers");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert(NW == 4, "four waves of 32 keys");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
     const uint32_t row_bytes = (uint32_t)(hd * 2);
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
     const char* Q = (const char*)((const bf16_t*)p.q + (q0 * p.H + h) * D);
     const char* DO = (const char*)((const bf16_t*)p.d_o + (q0 * p.H + h) * D);
+    const uint32_t lds0 = lds_address(lds);
 
     const int k_lo_w = wave * 32;
     int nk = nk_wg - k_lo_w;
@@ -332,23 +321,47 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         w_end = hi / KT + 1;
     }
 
-    IO io;
-    io.init(tid, row_bytes);
-    const int kr = r * PT::ROW_STRIDE + g * 16;
-    const int vr = (4 * g + ((lane & 15) >> 2)) * PT::TR_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    // stage = Q tile | dO tile (both in the two-way swizzle) | lse and delta of the tile's queries
+    TileDma<D, NW, SWZ_U> dma;
+    dma.init(lane, wave, row_bytes);
+    constexpr int LOADS_PER_TILE = 2 * TileDma<D, NW, SWZ_U>::IPW + (SOFTMAX ? 2 : 0);
+    u32x4 lse_rsrc = {0, 0, 0, 0}, delta_rsrc = {0, 0, 0, 0};
+    if (SOFTMAX && nq_all > 0) {
+        const int64_t first = (int64_t)h * p.total_q + q0;
+        lse_rsrc = make_rsrc_words(p.lse + first, (uint32_t)nq_all * 4);
+        delta_rsrc = make_rsrc_words(delta_ws + first, (uint32_t)nq_all * 4);
+    }
+    auto issue = [&](int qt, int stage) {
+        const uint32_t dst = lds0 + stage * SM::STAGE;
+        dma.issue(Q + qt * tile_bytes, nq_all - qt * KT, dst);
+        dma.issue(DO + qt * tile_bytes, nq_all - qt * KT, dst + SM::TILE);
+        if (SOFTMAX) {  // every wave sends the same two loads (equal load counts in all waves); indices clamped
+            const int qi = qt * KT + lane;
+            const uint32_t voff = (uint32_t)(qi < nq_all ? qi : nq_all - 1) * 4;
+            load_to_lds_b32(lse_rsrc, voff, 0, dst + 2 * SM::TILE);
+            load_to_lds_b32(delta_rsrc, voff, 0, dst + 2 * SM::TILE + 256);
+        }
+    };
+    const int n_steps = qt_end - qt_begin;
+    if (n_steps > 0) issue(qt_begin, 0);
 
-    // K^T and V^T fragments of this wave's keys (B operands: column = key r), via LDS
+    // K^T and V^T fragments of this wave's keys (B operands: column = key r), via the end of the ring
     bf16x8 kf[KC], vf[KC];
-    stage_rows<D, NW>(lds, (const bf16_t*)p.k, k_row0, nk_wg, h, p.H, io);
-    __syncthreads();
+    {
+        char* own = lds + SM::TOTAL - SM::OWN_BYTES;
+        const int64_t goff = k_row0 * hd + (int64_t)h * D;
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.k + goff), row_bytes, nk_wg, tid);
+        __syncthreads();
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) kf[kc] = *(const bf16x8*)(lds + k_lo_w * PT::ROW_STRIDE + kr + 32 * kc);
-    __syncthreads();
-    stage_rows<D, NW>(lds, (const bf16_t*)p.v, k_row0, nk_wg, h, p.H, io);
-    __syncthreads();
+        for (int kc = 0; kc < KC; ++kc) kf[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+        __syncthreads();
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.v + goff), row_bytes, nk_wg, tid);
+        __syncthreads();
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) vf[kc] = *(const bf16x8*)(lds + k_lo_w * PT::ROW_STRIDE + kr + 32 * kc);
-    __syncthreads();
+        for (int kc = 0; kc < KC; ++kc) vf[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+        __syncthreads();
+    }
+    if (n_steps > 1) issue(qt_begin + 1, 1);
 
     // queries that see this lane's key: q_lo .. q_lo + q_span (empty for padding lanes)
     int q_lo;
@@ -371,76 +384,75 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dkacc[db][v] = 0.f; dvacc[db][v] = 0.f; }
     const float sc = SOFTMAX ? p.scale * LOG2E_T : p.scale;
+    UFrag<D> uf;
+    uf.init(lane);
 
-    u32x4 qst[IO::LOADS], dst[IO::LOADS];
-    float st_lse = INFINITY, st_delta = 0.f;
-    auto fetch = [&](int qt) {
-        if (qt < qt_end) {
-            io.load(qst, Q + qt * tile_bytes, nq_all - qt * KT);
-            io.load(dst, DO + qt * tile_bytes, nq_all - qt * KT);
-            if (SOFTMAX && tid < KT) {
-                const int qi = qt * KT + tid;
-                st_lse = INFINITY;  // weight exp2(s - inf) = 0 for rows past the end
-                st_delta = 0.f;
-                if (qi < nq_all) {
-                    const int64_t idx = (int64_t)h * p.total_q + q0 + qi;
-                    st_lse = p.lse[idx] * LOG2E_T;
-                    st_delta = delta_ws[idx];
-                }
-            }
+    int stage = 0;
+    for (int i = 0; i < n_steps; ++i) {
+        if (i + 1 < n_steps) wait_vmcnt<LOADS_PER_TILE>();
+        else wait_vmcnt<0>();
+        __syncthreads();  // tile i complete; every wave is done with the stage of tile i-1
+        const char* ldsQ = lds + stage * SM::STAGE;
+        const char* ldsDO = ldsQ + SM::TILE;
+        const float* stats = (const float*)(ldsDO + SM::TILE);
+        const int free_stage = stage == 0 ? 2 : stage - 1;
+        stage = stage == 2 ? 0 : stage + 1;
+        const int qt = qt_begin + i;
+        // The loads of tile i+2 go out AFTER the work on tile i: this kernel keeps a few values in
+        // scratch memory at d = 128, the compiler waits for "all" vector-memory operations around
+        // their reloads, and loads sent before the work would be waited for right away.
+        if (!wave_active || qt < w_begin || qt >= w_end) {
+            if (i + 2 < n_steps) issue(qt_begin + i + 2, free_stage);
+            continue;
         }
-    };
-    fetch(qt_begin);
-    for (int qt = qt_begin; qt < qt_end; ++qt) {
-        char* ldsQ = lds + ((qt - qt_begin) & 1) * SM::BUF;
-        char* ldsQt = ldsQ + PT::ROW_TILE;
-        char* ldsDO = ldsQt + PT::TR_TILE;
-        char* ldsDOt = ldsDO + PT::ROW_TILE;
-        float* stats = (float*)(ldsDOt + PT::TR_TILE);
-        io.store_row(ldsQ, qst);
-        io.store_tr(ldsQt, qst);
-        io.store_row(ldsDO, dst);
-        io.store_tr(ldsDOt, dst);
-        if (SOFTMAX && tid < KT) { stats[tid] = st_lse; stats[KT + tid] = st_delta; }
-        __syncthreads();  // tile qt complete; every wave is done with the other buffer
-        fetch(qt + 1);
-        if (!wave_active || qt < w_begin || qt >= w_end) continue;
         // S = Q K^T and dP = dO V^T: lane = key column, registers = queries of the tile
         f32x16 sacc, dpacc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dpacc[v] = 0.f; }
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) {
-            const bf16x8 qa = *(const bf16x8*)(ldsQ + kr + 32 * kc);
-            const bf16x8 da = *(const bf16x8*)(ldsDO + kr + 32 * kc);
+            const bf16x8 qa = uf.row(ldsQ, kc);
+            const bf16x8 da = uf.row(ldsDO, kc);
             sacc = mfma32(qa, kf[kc], sacc);
             dpacc = mfma32(da, vf[kc], dpacc);
         }
-        const unsigned rel0 = (unsigned)(qt * KT + 4 * g - q_lo);
+        // Interior tiles - every (query, key) pair inside the sequence and the window - skip the
+        // visibility test.  (Padding key lanes hold zero K/V rows and are never stored.)
+        const int q_base = qt * KT;
+        bool need_mask = q_base + KT > nq_all;
+        if (WINDOWED) {
+            const int kp_lo = kpos_w, kp_hi = kpos_w + nk - 1;
+            if (p.right >= 0 && q_base < kp_hi - p.right) need_mask = true;
+            if (p.left >= 0 && q_base + KT - 1 > kp_lo + p.left) need_mask = true;
+        }
         float pv[16], dsv[16];
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
             f32x4 lse4 = {0.f, 0.f, 0.f, 0.f}, del4 = {0.f, 0.f, 0.f, 0.f};
-            if (SOFTMAX) {
+            if (SOFTMAX) {  // natural-log LSE of queries 8*vg + 4g + 0..3 of the tile, and their delta
                 lse4 = *(const f32x4*)(stats + 8 * vg + 4 * g);
-                del4 = *(const f32x4*)(stats + KT + 8 * vg + 4 * g);
+                del4 = *(const f32x4*)(stats + 64 + 8 * vg + 4 * g);
             }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int v = 4 * vg + e;
-                const float s = sacc[v] * sc;
-                float val, ds;
                 if (SOFTMAX) {
-                    val = fast_exp2(s - lse4[e]);
-                    ds = val * (dpacc[v] - del4[e]) * p.scale;
+                    pv[v] = fast_exp2(fmaf(sacc[v], sc, lse4[e] * -LOG2E_T));
+                    dsv[v] = pv[v] * (dpacc[v] - del4[e]) * p.scale;
                 } else {
                     float der;
-                    act_fast_vd<ACT>(s, val, der);
-                    ds = dpacc[v] * der * p.scale;
+                    act_fast_vd<ACT>(sacc[v] * sc, pv[v], der);
+                    dsv[v] = dpacc[v] * der * p.scale;
                 }
-                const bool ok = rel0 + (unsigned)(8 * vg + e) <= q_span;
-                pv[v] = ok ? val : 0.f;
-                dsv[v] = ok ? ds : 0.f;
+            }
+        }
+        if (need_mask) {
+            const unsigned rel0 = (unsigned)(q_base + 4 * g - q_lo);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= q_span;
+                pv[v] = ok ? pv[v] : 0.f;
+                dsv[v] = ok ? dsv[v] : 0.f;
             }
         }
         bf16x8 pf[2], dsf[2];
@@ -453,41 +465,19 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                dvacc[db] = mfma32(tr_frag<D>(ldsDOt, vr, db, c), pf[c], dvacc[db]);
-                dkacc[db] = mfma32(tr_frag<D>(ldsQt, vr, db, c), dsf[c], dkacc[db]);
+                dvacc[db] = mfma32(uf.transposed(ldsDO, db, c), pf[c], dvacc[db]);
+                dkacc[db] = mfma32(uf.transposed(ldsQ, db, c), dsf[c], dkacc[db]);
             }
+        if (i + 2 < n_steps) issue(qt_begin + i + 2, free_stage);
     }
-    __syncthreads();  // every wave is done with the tile buffers
+    __syncthreads();  // every wave is done with the ring
     if (!wave_active) return;
-    char* stage = lds + wave * PT::ROW_TILE;
-    store_tile_rows<D>(stage, dvacc, (bf16_t*)p.dv + (k_row0 + k_lo_w) * hd + (int64_t)h * D, hd, nk, lane);
-    store_tile_rows<D>(stage, dkacc, (bf16_t*)p.dk + (k_row0 + k_lo_w) * hd + (int64_t)h * D, hd, nk, lane);
+    char* out_stage = lds + wave * PT::ROW_TILE;
+    store_tile_rows<D>(out_stage, dvacc, (bf16_t*)p.dv + (k_row0 + k_lo_w) * hd + (int64_t)h * D, hd, nk, lane);
+    store_tile_rows<D>(out_stage, dkacc, (bf16_t*)p.dk + (k_row0 + k_lo_w) * hd + (int64_t)h * D, hd, nk, lane);
 }
 
 // ------------------------------------------------------------------ kernels
-
-// items = (example, head, tile) in that order, cut into 8 contiguous ranges, one per XCD
-// (workgroup i runs on XCD i % 8); tile_start[b] = number of tiles before example b.
-__device__ __forceinline__ bool locate_item(const int32_t* __restrict__ tile_start, int B, int H, int& b, int& h, int& t) {
-    const int64_t n_items = (int64_t)tile_start[B] * H;
-    const int64_t per_xcd = (n_items + 7) / 8;
-    const int xcd = blockIdx.x & 7;
-    const int64_t slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return false;
-    const int64_t item = xcd * per_xcd + slot;
-    if (item >= n_items) return false;
-    int lo = 0, hi = B - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if ((int64_t)tile_start[mid] * H <= item) lo = mid; else hi = mid - 1;
-    }
-    b = lo;
-    const int nt = tile_start[b + 1] - tile_start[b];
-    const int64_t rem = item - (int64_t)tile_start[b] * H;
-    h = (int)(rem / nt);
-    t = (int)(rem % nt);
-    return true;
-}
 
 #define KUNLUN_ACT_SWITCH(ACTV, CALL)                                   \
     switch (ACTV) {                                                     \
@@ -499,12 +489,15 @@ __device__ __forceinline__ bool locate_item(const int32_t* __restrict__ tile_sta
     default: { constexpr int A = KUNLUN_ACT_SILU; CALL; } break;                        \
     }
 
+// work mapping of tile_map.h in both passes
 template <int D, int NW, bool WINDOWED>
-__global__ __launch_bounds__(64 * NW, 2) void bwd_dq_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dq_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+                                                            const int32_t* __restrict__ tile_example, int runs,
                                                             const float* __restrict__ delta_ws) {
-    __shared__ __attribute__((aligned(1024))) char lds[DqSmem<D>::TOTAL];
+    __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, 0>::TOTAL];
+    static_assert(32 * NW == TILE_ROWS, "tile size of the work mapping");
     int b, h, qt;
-    if (!locate_item(tile_start, p.B, p.H, b, h, qt)) return;
+    if (!locate_tile(tile_start, tile_example, p.B, p.H, runs, b, h, qt)) return;
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
     const int64_t q0 = q_begin(p, b);
@@ -519,11 +512,12 @@ __global__ __launch_bounds__(64 * NW, 2) void bwd_dq_kernel(AttnParams p, const 
 }
 
 template <int D, int NW, bool WINDOWED>
-__global__ __launch_bounds__(64 * NW, 2) void bwd_dkdv_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dkdv_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+                                                              const int32_t* __restrict__ tile_example, int runs,
                                                               const float* __restrict__ delta_ws) {
-    extern __shared__ __attribute__((aligned(1024))) char lds[];  // DkvSmem<D>::TOTAL bytes (above 64 KB at D = 128)
+    __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, STATS_BYTES>::TOTAL];
     int b, h, kt;
-    if (!locate_item(tile_start, p.B, p.H, b, h, kt)) return;
+    if (!locate_tile(tile_start, tile_example, p.B, p.H, runs, b, h, kt)) return;
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
     const int64_t q0 = q_begin(p, b);
@@ -561,72 +555,37 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t* __restrict__ o
     }
 }
 
-// Exclusive prefix sum of ceil(len_b / tile) over the examples (off == null: dense_len rows each).
-__global__ __launch_bounds__(1024) void bwd_tile_prefix_kernel(const int32_t* __restrict__ off, int dense_len, int B,
-                                                               int tile, int32_t* __restrict__ tile_start) {
-    __shared__ int part[1024];
-    const int tid = threadIdx.x;
-    const int per = (B + 1023) / 1024;
-    const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
-    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + tile - 1) / tile; };
-    int sum = 0;
-    for (int b = b0; b < b1; ++b) sum += tiles_of(b);
-    part[tid] = sum;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        const int v = tid >= o ? part[tid - o] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - sum;
-    for (int b = b0; b < b1; ++b) {
-        tile_start[b] = run;
-        run += tiles_of(b);
-    }
-    if (tid == 1023) tile_start[B] = part[1023];
-}
-
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype) {
     return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128);
 }
 
-size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q) {
-    return 2 * align_up((size_t)(B + 1) * sizeof(int32_t), 256) + align_up((size_t)H * total_q * sizeof(float), 256);
+size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv) {
+    return tile_table_bytes(B, total_q) + tile_table_bytes(B, total_kv) + align_up((size_t)H * total_q * sizeof(float), 256);
 }
 
 template <int D, bool WINDOWED>
 static hipError_t launch_tiled(const AttnParams& p, char* ws, bool any_softmax, hipStream_t stream) {
-    constexpr int NW = 4, TILE = 32 * NW;
-    const size_t pre = align_up((size_t)(p.B + 1) * sizeof(int32_t), 256);
+    constexpr int NW = 4;
     int32_t* q_tiles = (int32_t*)ws;
-    int32_t* k_tiles = (int32_t*)(ws + pre);
-    float* delta = (float*)(ws + 2 * pre);
+    int32_t* k_tiles = (int32_t*)(ws + tile_table_bytes(p.B, p.total_q));
+    float* delta = (float*)(ws + tile_table_bytes(p.B, p.total_q) + tile_table_bytes(p.B, p.total_kv));
+    const int runs = tile_runs(WINDOWED, p.left, p.right, p.H);
     if (any_softmax && p.total_q > 0) {
         const int64_t threads = p.total_q * p.H * (D / 8);
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            (const bf16_t*)p.o, (const bf16_t*)p.d_o, delta, p.total_q, p.H);
     }
     if (p.total_q > 0) {
-        hipLaunchKernelGGL(bwd_tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, TILE, q_tiles);
-        const int64_t per_xcd = ((p.total_q / TILE + p.B) * p.H + 7) / 8;
-        hipLaunchKernelGGL((bwd_dq_kernel<D, NW, WINDOWED>), dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), 0, stream, p,
-                           q_tiles, delta);
+        hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, q_tiles,
+                           tile_example_of(q_tiles, p.B));
+        hipLaunchKernelGGL((bwd_dq_kernel<D, NW, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_q, runs)), dim3(64 * NW), 0,
+                           stream, p, q_tiles, tile_example_of(q_tiles, p.B), runs, delta);
     }
     if (p.total_kv > 0) {
-        hipLaunchKernelGGL(bwd_tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.kv_off, 0, p.B, TILE, k_tiles);
-        const int64_t per_xcd = ((p.total_kv / TILE + p.B) * p.H + 7) / 8;
-        auto kern = bwd_dkdv_kernel<D, NW, WINDOWED>;
-        constexpr int lds_bytes = DkvSmem<D>::TOTAL;
-        if (lds_bytes > 64 * 1024) {
-            static bool raised = false;  // once per process; not a stream operation
-            if (!raised) {
-                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-                if (e != hipSuccess) return e;
-                raised = true;
-            }
-        }
-        hipLaunchKernelGGL(kern, dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds_bytes, stream, p, k_tiles, delta);
+        hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.kv_off, 0, p.B, k_tiles,
+                           tile_example_of(k_tiles, p.B));
+        hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_kv, runs)), dim3(64 * NW), 0,
+                           stream, p, k_tiles, tile_example_of(k_tiles, p.B), runs, delta);
     }
     return hipGetLastError();
 }

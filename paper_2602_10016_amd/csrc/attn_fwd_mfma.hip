@@ -376,10 +376,10 @@ static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
 
 bool mfma_fwd_is_qtiled(const AttnParams& p) { return p.windowed || p.max_q > 64; }
 
-hipError_t launch_mfma_fwd(const AttnParams& p, void* workspace_tail, hipStream_t stream) {
+hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
     // 32 queries per wave, up to 255 registers per wave, two or three waves per SIMD.
     // Query-tiled launches use 128-query tiles (4 waves): fewer K/V tile loads per query.
-    if (mfma_fwd_is_qtiled(p)) return launch_mfma_fwd_qtiled(p, workspace_tail, stream);
+    if (mfma_fwd_is_qtiled(p)) return launch_mfma_fwd_qtiled(p, stream);
     if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
     return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
 }

@@ -8,15 +8,11 @@
 // registers, O^T += V^T P^T); what differs is how tiles travel.  A step of this kernel costs
 // one full memory round trip if only one tile is in flight, and the window makes steps many
 // and short, so the tiles are moved by the buffer-load-to-LDS path (no staging registers)
-// into a ring of three LDS stages: while tile t is consumed, tiles t+1 and t+2 are in flight.
-// The loads are written in assembly because the compiler would otherwise wait for ALL
-// outstanding loads before every LDS read; the kernel counts its own loads (vmcnt) instead.
-//
-// LDS tiles are unpadded (a load instruction writes 64 consecutive 16-byte slots) and bank
-// conflicts are avoided by an XOR swizzle that is applied on the global side: slot (row, pos)
-// of a K tile receives the 16-byte chunk pos ^ xk(row) of the row, of a V tile the chunk
-// pos ^ 4*xv(row) (TileLayout::k_offset / v_offset give the matching read addresses).
+// into a ring of three LDS stages: while tile t is consumed, tiles t+1 and t+2 are in flight
+// (lds_ring.h).  K tiles use the K swizzle, V tiles the V swizzle of TileLayout.
 #include "attn_fwd_score.h"
+#include "lds_ring.h"
+#include "tile_map.h"
 
 namespace kunlun {
 
@@ -36,29 +32,6 @@ struct RingSmem {
     static constexpr bool Q_COVERS_STAGE1 = Q_BYTES > STAGE;
 };
 
-// 128-bit buffer descriptor: base address, byte count, raw 32-bit addressing.
-__device__ __forceinline__ u32x4 make_rsrc_words(const void* base, uint32_t bytes) {
-    const uint64_t a = (uint64_t)base;
-    const u32x4 r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
-    return r;
-}
-
-// One wave-wide 16-byte-per-lane load from a buffer straight into LDS: lane l's 16 bytes land
-// at lds_addr + 16*l.  voff: per-lane byte offset, soff: uniform byte offset.  Counted by vmcnt.
-__device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
-}
-
-// s_waitcnt that waits only for the vector-memory counter to drop to n (other counters untouched).
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
 template <int D, int NW, int ACT, bool WINDOWED>
 __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq_wg,
                                                    int64_t t0_wg, int64_t k0, int n_kv) {
@@ -68,9 +41,7 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
     constexpr int KC = D / 16;
     constexpr int DB = D / 32;
     constexpr int CHUNKS = D / 8;
-    constexpr int RPI = 1024 / SM::ROW;            // rows written by one load instruction
-    constexpr int IPW = SM::TILE / 1024 / NW;      // load instructions per wave per tile and tensor
-    static_assert(IPW >= 1 && SM::TILE % (1024 * NW) == 0, "tile does not split evenly over the waves");
+    constexpr int IPW = TileDma<D, NW, SWZ_K>::IPW;  // load instructions per wave per tile and tensor
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -80,7 +51,7 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
     const char* K = (const char*)((const bf16_t*)p.k + (k0 * p.H + h) * D);
     const char* V = (const char*)((const bf16_t*)p.v + (k0 * p.H + h) * D);
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t lds0 = lds_address(lds);
 
     // this wave's queries
     const int q_lo_w = wave * 32;
@@ -105,44 +76,15 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
         w_end = (int)(hi / KT) + 1;
     }
 
-    // ---- tile transport.  Load instruction j = wave*IPW + i of a tile fills the LDS bytes
-    // [1024 j, 1024 (j+1)): rows RPI*j .. ; lane -> (row, slot) -> swizzled source chunk.
-    uint32_t k_voff[IPW], v_voff[IPW];
-    int src_row[IPW], k_chunk[IPW], v_chunk[IPW];
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-        const int row = (wave * IPW + i) * RPI + lane / CHUNKS, pos = lane % CHUNKS;
-        const int xk = (D == 128) ? (row & 15) : ((row >> 1) & 7);
-        const int xv = (D == 128) ? (row & 3) : ((row >> 1) & 1);
-        src_row[i] = row;
-        k_chunk[i] = (pos ^ xk) * 16;
-        v_chunk[i] = (pos ^ (xv << 2)) * 16;
-        k_voff[i] = (uint32_t)row * row_bytes + k_chunk[i];
-        v_voff[i] = (uint32_t)row * row_bytes + v_chunk[i];
-    }
-    // Every load stays inside the valid rows of its tile: rows past the end of the history
-    // fetch the last valid row again (finite data; their weights are zero).
+    // ---- tile transport
+    TileDma<D, NW, SWZ_K> kdma;
+    TileDma<D, NW, SWZ_V> vdma;
+    kdma.init(lane, wave, row_bytes);
+    vdma.init(lane, wave, row_bytes);
     auto issue = [&](int kt, int stage) {
-        const int rows_left = n_kv - kt * KT;
-        const int rows = rows_left < KT ? rows_left : KT;
-        const uint32_t bytes = (uint32_t)(rows - 1) * row_bytes + SM::ROW;
-        const u32x4 kr = make_rsrc_words(K + kt * tile_bytes, bytes);
-        const u32x4 vr = make_rsrc_words(V + kt * tile_bytes, bytes);
-        const uint32_t dst = lds0 + stage * SM::STAGE + wave * IPW * 1024;
-        if (rows == KT) {
-#pragma unroll
-            for (int i = 0; i < IPW; ++i) {
-                load_to_lds_b128(kr, k_voff[i], 0, dst + i * 1024);
-                load_to_lds_b128(vr, v_voff[i], 0, dst + SM::TILE + i * 1024);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < IPW; ++i) {
-                const uint32_t rb = (uint32_t)(src_row[i] < rows ? src_row[i] : rows - 1) * row_bytes;
-                load_to_lds_b128(kr, rb + k_chunk[i], 0, dst + i * 1024);
-                load_to_lds_b128(vr, rb + v_chunk[i], 0, dst + SM::TILE + i * 1024);
-            }
-        }
+        const uint32_t dst = lds0 + stage * SM::STAGE;
+        kdma.issue(K + kt * tile_bytes, n_kv - kt * KT, dst);
+        vdma.issue(V + kt * tile_bytes, n_kv - kt * KT, dst + SM::TILE);
     };
 
     // ---- prologue.  The first key tile starts its journey at once (stage 0); the query tile
@@ -151,25 +93,10 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
     const int n_steps = kt_end - kt_begin;
     if (n_steps > 0) issue(kt_begin, 0);
     if (!SM::Q_COVERS_STAGE1 && n_steps > 1) issue(kt_begin + 1, 1);
-    constexpr int Q_LOADS = SM::QT * CHUNKS / (64 * NW);
     bf16x8 qf[KC];
     {
         char* qstage = lds + SM::TOTAL - SM::Q_BYTES;
-        const char* qbase = (const char*)((const bf16_t*)p.q + q_row0 * hd + (int64_t)h * D);
-        const __amdgpu_buffer_rsrc_t qrsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void*)qbase, 0, (nq_wg - 1) * (int)row_bytes + D * 2, 0x00020000);
-        u32x4 qst[Q_LOADS];
-        constexpr int ROWS_PER_LOAD = 64 * NW / CHUNKS;
-        const int qrow = tid / CHUNKS, qch = tid % CHUNKS;
-#pragma unroll
-        for (int i = 0; i < Q_LOADS; ++i)  // rows past the tile read as zero
-            qst[i] = __builtin_amdgcn_raw_buffer_load_b128(qrsrc, (uint32_t)qrow * row_bytes + qch * 16,
-                                                           i * ROWS_PER_LOAD * row_bytes, 0);
-#pragma unroll
-        for (int i = 0; i < Q_LOADS; ++i) {
-            const int row = i * ROWS_PER_LOAD + qrow;  // the swizzle has period 16 (or 32) rows
-            *(u32x4*)(qstage + (row / KT) * SM::TILE + L::k_offset(row % KT, qch)) = qst[i];
-        }
+        stage_rows_swizzled<D, NW>(qstage, (const char*)((const bf16_t*)p.q + q_row0 * hd + (int64_t)h * D), row_bytes, nq_wg, tid);
         __syncthreads();
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc)
@@ -301,34 +228,15 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
     }
 }
 
-// Query-tiled launch: grid = H * (query tiles of all examples), cut into 8 contiguous ranges,
-// one per XCD (workgroup i runs on XCD i % 8), so that the query tiles of one (example, head)
-// - which share their keys - meet in the same L2.  Items are ordered by example, then query
-// tile, then head.  tile_start[b] = number of query tiles before example b and tile_example[t]
-// = example of query tile t (both written by the prefix kernel), so a workgroup finds its
-// item with two dependent loads.
-// An XCD's range is further cut into `runs` contiguous runs that are issued round-robin:
-// workgroups that follow each other in a run start `runs` slots apart, so that the next query
-// tile of an (example, head) starts when its predecessor is about one tile width into its
-// window and both read the keys they share at about the same time.
+// One workgroup per (example, query tile, head); work mapping of tile_map.h.
 template <int D, int NW, int OCC, bool WINDOWED>
 __global__ __launch_bounds__(64 * NW, OCC) void qtile_fwd_mfma_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                                       const int32_t* __restrict__ tile_example, int runs) {
     __shared__ __attribute__((aligned(1024))) char lds[RingSmem<D, NW>::TOTAL];
     constexpr int QT = 32 * NW;
-    const int64_t n_items = (int64_t)tile_start[p.B] * p.H;
-    const int64_t per_xcd = (n_items + 7) / 8;
-    const int xcd = blockIdx.x & 7;
-    const int64_t slot = blockIdx.x >> 3;
-    const int64_t run_len = (per_xcd + runs - 1) / runs;
-    const int64_t in_xcd = (slot % runs) * run_len + slot / runs;
-    if (slot >= run_len * runs || in_xcd >= per_xcd) return;
-    const int64_t item = xcd * per_xcd + in_xcd;
-    if (item >= n_items) return;
-    const int tile = (int)(item / p.H);
-    const int h = (int)(item % p.H);
-    const int b = tile_example[tile];
-    const int qt = tile - tile_start[b];
+    static_assert(QT == TILE_ROWS, "tile size of the work mapping");
+    int b, h, qt;
+    if (!locate_tile(tile_start, tile_example, p.B, p.H, runs, b, h, qt)) return;
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
     const int64_t q0 = q_begin(p, b);
@@ -349,73 +257,23 @@ __global__ __launch_bounds__(64 * NW, OCC) void qtile_fwd_mfma_kernel(AttnParams
     }
 }
 
-// Exclusive prefix sum of ceil(len_b / tile) over the examples, and the example of every tile;
-// single workgroup.  off == null: every example has `dense_len` rows.
-__global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int dense_len, int B,
-                                                           int tile, int32_t* __restrict__ tile_start,
-                                                           int32_t* __restrict__ tile_example) {
-    __shared__ int part[1024];
-    const int tid = threadIdx.x;
-    const int per = (B + 1023) / 1024;
-    const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
-    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + tile - 1) / tile; };
-    int sum = 0;
-    for (int b = b0; b < b1; ++b) sum += tiles_of(b);
-    part[tid] = sum;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        const int v = tid >= o ? part[tid - o] : 0;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
-    }
-    int run = part[tid] - sum;
-    for (int b = b0; b < b1; ++b) {
-        tile_start[b] = run;
-        const int n = tiles_of(b);
-        for (int t = 0; t < n; ++t) tile_example[run + t] = b;
-        run += n;
-    }
-    if (tid == 1023) tile_start[B] = part[1023];
-}
-
-size_t mfma_fwd_qtiled_workspace(int B, int64_t total_q) {
-    return align_up((size_t)(total_q / 128 + B) * sizeof(int32_t), 256);  // tile_example
-}
-
 template <int D, int NW, int OCC, bool WINDOWED>
-static hipError_t launch_qtiled(const AttnParams& p, void* workspace_tail, hipStream_t stream) {
-    // an upper bound of the query-tile count sizes the grid
-    constexpr int QT = 32 * NW;
-    static_assert(QT == 128, "mfma_fwd_qtiled_workspace assumes 128-query tiles");
-    const int64_t max_tiles = p.total_q / QT + p.B;
-    const int64_t per_xcd = (max_tiles * p.H + 7) / 8;
-    // Window of finite reach: a tile shares keys with (reach / QT) neighbours on each side.  With
-    // about 96 workgroups resident per XCD, the next tile of an (example, head) - H items
-    // further in item order - should start 96 / (neighbours + 1) slots later.
-    int runs = 1;
-    if (WINDOWED && p.left >= 0 && p.right >= 0) {
-        const int64_t span_tiles = ((int64_t)p.left + p.right + QT - 1) / QT + 1;
-        const int64_t want = 96 / span_tiles / p.H;
-        runs = (int)(want < 1 ? 1 : (want > 32 ? 32 : want));
-    }
-    const unsigned grid = (unsigned)((per_xcd + runs) * 8);
+static hipError_t launch_qtiled(const AttnParams& p, hipStream_t stream) {
+    const int runs = tile_runs(WINDOWED, p.left, p.right, p.H);
     int32_t* tile_start = const_cast<int32_t*>(p.order);
-    int32_t* tile_example = (int32_t*)workspace_tail;
-    hipLaunchKernelGGL(tile_prefix_kernel, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, QT, tile_start,
+    int32_t* tile_example = tile_example_of(tile_start, p.B);
+    hipLaunchKernelGGL(tile_prefix_kernel<0>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, tile_start,
                        tile_example);
-    hipLaunchKernelGGL((qtile_fwd_mfma_kernel<D, NW, OCC, WINDOWED>), dim3(grid), dim3(64 * NW), 0, stream, p, tile_start,
-                       tile_example, runs);
+    hipLaunchKernelGGL((qtile_fwd_mfma_kernel<D, NW, OCC, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_q, runs)),
+                       dim3(64 * NW), 0, stream, p, tile_start, tile_example, runs);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, void* workspace_tail, hipStream_t stream) {
+// p.order points at tile_table_bytes(B, total_q) bytes of workspace.
+hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, hipStream_t stream) {
     // 128-query tiles (4 waves of 32 queries)
-    if (p.windowed)
-        return p.d == 128 ? launch_qtiled<128, 4, 2, true>(p, workspace_tail, stream)
-                          : launch_qtiled<64, 4, 2, true>(p, workspace_tail, stream);
-    return p.d == 128 ? launch_qtiled<128, 4, 2, false>(p, workspace_tail, stream)
-                      : launch_qtiled<64, 4, 2, false>(p, workspace_tail, stream);
+    if (p.windowed) return p.d == 128 ? launch_qtiled<128, 4, 2, true>(p, stream) : launch_qtiled<64, 4, 2, true>(p, stream);
+    return p.d == 128 ? launch_qtiled<128, 4, 2, false>(p, stream) : launch_qtiled<64, 4, 2, false>(p, stream);
 }
 
 }  // namespace kunlun

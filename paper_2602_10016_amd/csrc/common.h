@@ -43,13 +43,12 @@ bool schedule_is_moot(int64_t workgroups, int wgs_per_cu);
 hipError_t launch_scalar_fwd(const AttnParams& p, int dtype, hipStream_t stream);
 hipError_t launch_scalar_bwd(const AttnParams& p, int dtype, hipStream_t stream);
 bool mfma_fwd_supported(const AttnParams& p, int dtype);
-hipError_t launch_mfma_fwd(const AttnParams& p, void* workspace_tail, hipStream_t stream);
+hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream);
 // True when the forward launch walks query tiles (window op, or more than 64 queries per
 // example): the workspace then holds query-tile prefix sums instead of the sorted example order.
 bool mfma_fwd_is_qtiled(const AttnParams& p);
-// workspace_tail: mfma_fwd_qtiled_workspace bytes behind the prefix sums (example of every query tile)
-size_t mfma_fwd_qtiled_workspace(int B, int64_t total_q);
-hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, void* workspace_tail, hipStream_t stream);
+// p.order points at tile_table_bytes(B, total_q) bytes (tile_map.h): prefix sums, then the example of every query tile
+hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, hipStream_t stream);
 bool mfma_bwd_supported(const AttnParams& p, int dtype);
 hipError_t launch_mfma_bwd(const AttnParams& p, void* workspace_tail, hipStream_t stream);
 size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
@@ -57,7 +56,7 @@ size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
 hipError_t launch_mfma_bwd_pair(const AttnParams& p, hipStream_t stream);
 // Two-pass matrix-core backward (sliding window, or more than 64 queries per example).
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype);
-size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q);
+size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv);
 hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool any_softmax, hipStream_t stream);
 
 #ifdef __HIPCC__
