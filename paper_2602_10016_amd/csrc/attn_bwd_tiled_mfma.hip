@@ -288,6 +288,11 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
     using SM = TiledSmem<D, STATS_BYTES>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16, DB = D / 32;
+    // At d = 128 the accumulators (128 registers) and the K^T, V^T fragments (64) leave too little
+    // room for the rest; values parked in scratch memory would be reloaded with vector-memory
+    // loads inside the loop, and the compiler waits for those together with the tile loads in flight.  The last K_LDS
+    // K^T fragments of every wave are parked in LDS instead, lane by lane, behind the ring.
+    constexpr int K_LDS = D == 128 ? 3 : 0, K_REG = KC - K_LDS;
     static_assert(NW == 4, "four waves of 32 keys");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -346,14 +351,19 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
     if (n_steps > 0) issue(qt_begin, 0);
 
     // K^T and V^T fragments of this wave's keys (B operands: column = key r), via the end of the ring
-    bf16x8 kf[KC], vf[KC];
+    bf16x8 kf[K_REG], vf[KC];
+    char* kpark = lds + SM::TOTAL + (wave * K_LDS * 64 + lane) * 16;  // + 1024 per fragment
     {
         char* own = lds + SM::TOTAL - SM::OWN_BYTES;
         const int64_t goff = k_row0 * hd + (int64_t)h * D;
         stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.k + goff), row_bytes, nk_wg, tid);
         __syncthreads();
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) kf[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 f = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+            if (kc < K_REG) kf[kc < K_REG ? kc : 0] = f;
+            else *(bf16x8*)(kpark + (kc - K_REG) * 1024) = f;
+        }
         __syncthreads();
         stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.v + goff), row_bytes, nk_wg, tid);
         __syncthreads();
@@ -398,13 +408,8 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         const int free_stage = stage == 0 ? 2 : stage - 1;
         stage = stage == 2 ? 0 : stage + 1;
         const int qt = qt_begin + i;
-        // The loads of tile i+2 go out AFTER the work on tile i: this kernel keeps a few values in
-        // scratch memory at d = 128, the compiler waits for "all" vector-memory operations around
-        // their reloads, and loads sent before the work would be waited for right away.
-        if (!wave_active || qt < w_begin || qt >= w_end) {
-            if (i + 2 < n_steps) issue(qt_begin + i + 2, free_stage);
-            continue;
-        }
+        if (i + 2 < n_steps) issue(qt_begin + i + 2, free_stage);
+        if (!wave_active || qt < w_begin || qt >= w_end) continue;
         // S = Q K^T and dP = dO V^T: lane = key column, registers = queries of the tile
         f32x16 sacc, dpacc;
 #pragma unroll
@@ -413,9 +418,11 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         for (int kc = 0; kc < KC; ++kc) {
             const bf16x8 qa = uf.row(ldsQ, kc);
             const bf16x8 da = uf.row(ldsDO, kc);
-            sacc = mfma32(qa, kf[kc], sacc);
+            const bf16x8 kb = kc < K_REG ? kf[kc < K_REG ? kc : 0] : *(const bf16x8*)(kpark + (kc - K_REG) * 1024);
+            sacc = mfma32(qa, kb, sacc);
             dpacc = mfma32(da, vf[kc], dpacc);
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the LDS reads of the next phase behind this one (register pressure)
         // Interior tiles - every (query, key) pair inside the sequence and the window - skip the
         // visibility test.  (Padding key lanes hold zero K/V rows and are never stored.)
         const int q_base = qt * KT;
@@ -460,6 +467,7 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         for (int c = 0; c < 2; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) { pf[c][e] = (bf16_t)pv[8 * c + e]; dsf[c][e] = (bf16_t)dsv[8 * c + e]; }
+        __builtin_amdgcn_sched_barrier(0);
         // dV^T += dO^T P and dK^T += Q^T dS (contraction over the queries of the tile)
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -468,7 +476,6 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
                 dvacc[db] = mfma32(uf.transposed(ldsDO, db, c), pf[c], dvacc[db]);
                 dkacc[db] = mfma32(uf.transposed(ldsQ, db, c), dsf[c], dkacc[db]);
             }
-        if (i + 2 < n_steps) issue(qt_begin + i + 2, free_stage);
     }
     __syncthreads();  // every wave is done with the ring
     if (!wave_active) return;
@@ -515,7 +522,7 @@ template <int D, int NW, bool WINDOWED>
 __global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dkdv_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                               const int32_t* __restrict__ tile_example, int runs,
                                                               const float* __restrict__ delta_ws) {
-    __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, STATS_BYTES>::TOTAL];
+    __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, STATS_BYTES>::TOTAL + (D == 128 ? 3 : 0) * NW * 1024];
     int b, h, kt;
     if (!locate_tile(tile_start, tile_example, p.B, p.H, runs, b, h, kt)) return;
     const int64_t k0 = p.kv_off[b];
