@@ -1,20 +1,21 @@
-// bf16 matrix-core forward kernels for gfx950: GDPA (Eq. (GDPA)), softmax attention of a few
-// seed / context queries over a jagged history (Eq. (PMA), Eq. (seed-level attention)) and
-// sliding-window self-attention (Eq. (sliding window)).
+// bf16 matrix-core forward kernel for gfx950, streaming launches: GDPA (Eq. (GDPA)) and softmax
+// attention of a few seed / context queries (up to 64 per example) over a jagged history
+// (Eq. (PMA), Eq. (seed-level attention)).  Longer query sequences and the sliding window are
+// served by the query-tiled kernel (attn_fwd_ring_mfma.hip).
 //
-// A workgroup of NW wavefronts owns one work item = (example, head, tile of 32*NQB*NW
-// queries); each wave owns 32*NQB of those queries for the whole item.  The waves stream the
-// 32-key K/V tiles of the item together: every thread fetches its share of tile t+1 into
-// registers (whole rows, coalesced) while tile t, already in LDS, is being consumed; tiles
-// are double-buffered in LDS, so there is one barrier per tile.  These operators do only
-// Nq flops per byte of K/V (a key/value byte is used by the queries of its own example and
-// head and by nobody else), far below the matrix-core ridge, so the design goal is bytes in
-// flight and enough resident waves to hide latency, not MFMA occupancy.
+// A workgroup of NW wavefronts owns one work item = (example, head); each wave owns 32*NQB of
+// its queries for the whole item.  The waves stream the 32-key K/V tiles of the item together:
+// every thread fetches its share of tile t+1 (and t+2) into registers (whole rows, coalesced,
+// non-temporal) while tile t, already in LDS, is being consumed; tiles are double-buffered in
+// LDS, so there is one barrier per tile.  These operators do only Nq flops per byte of K/V (a
+// key/value byte is used by the queries of its own example and head and by nobody else), far
+// below the matrix-core ridge, so the design goal is bytes in flight and enough resident waves
+// to hide latency, not MFMA occupancy.
 //
 // Per 32-key tile and wave:
 //     S^T = K Q^T              (MFMA; Q^T fragments resident in registers)
-//     P^T = score function of S^T * scale, in registers, zero past the end of the history /
-//           outside the window, packed to bf16
+//     P^T = score function of S^T * scale, in registers, zero past the end of the history,
+//           packed to bf16
 //     O^T += V^T P^T           (MFMA; V^T via transposing LDS reads)
 // Softmax keeps a running maximum and sum per query (one query per lane column) and rescales
 // O^T when the maximum grows; the activation path has no such stage.
@@ -86,11 +87,10 @@ struct CoopTile {
     }
 };
 
-// One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's
-// tile; t0_wg: position of that first query inside its sequence (sliding window only).
-template <int D, int NQB, int NW, int ACT, bool WINDOWED>
+// One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's tile.
+template <int D, int NQB, int NW, int ACT>
 __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq_wg,
-                                              int64_t t0_wg, int64_t k0, int n_kv) {
+                                              int64_t k0, int n_kv) {
     using SM = FwdSmem<D>;
     using CT = CoopTile<D, NW>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
@@ -112,23 +112,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     int nq = nq_wg - q_lo_w;
     nq = nq < 0 ? 0 : (nq > QW ? QW : nq);
     const bool wave_active = nq > 0;
-    const int64_t t0 = t0_wg + q_lo_w;
-
-    // key tiles of the workgroup, and of this wave
-    int kt_begin = 0, kt_end = (n_kv + KT - 1) / KT;
-    int w_begin = 0, w_end = kt_end;
-    if (WINDOWED && n_kv > 0) {
-        int64_t lo = 0, hi = n_kv - 1;
-        if (p.left >= 0 && t0_wg - p.left > lo) lo = t0_wg - p.left;
-        if (p.right >= 0 && t0_wg + nq_wg - 1 + p.right < hi) hi = t0_wg + nq_wg - 1 + p.right;
-        kt_begin = (int)(lo / KT);
-        kt_end = (int)(hi / KT) + 1;
-        lo = 0; hi = n_kv - 1;
-        if (p.left >= 0 && t0 - p.left > lo) lo = t0 - p.left;
-        if (p.right >= 0 && t0 + nq - 1 + p.right < hi) hi = t0 + nq - 1 + p.right;
-        w_begin = (int)(lo / KT);
-        w_end = (int)(hi / KT) + 1;
-    }
+    const int kt_end = (n_kv + KT - 1) / KT;  // key tiles of the item
 
     CT ct;
     ct.init(tid, row_bytes);
@@ -167,22 +151,9 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         if (NW > 1) __syncthreads();  // the tile buffers are reused for K/V from here on
     }
 
-    // visible keys of this lane's query: key_lo .. key_lo + key_span (an empty range for padding
-    // lanes whose query lies past the end)
-    int key_lo[NQB];
-    unsigned key_span[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const int tq = (int)t0 + 32 * qb + r;
-        int lo = 0, hi = n_kv - 1;
-        if (WINDOWED) {
-            if (p.left >= 0 && tq - p.left > lo) lo = tq - p.left;
-            if (p.right >= 0 && tq + p.right < hi) hi = tq + p.right;
-        }
-        const bool empty = hi < lo;
-        key_lo[qb] = empty ? 0x3fffffff : lo;
-        key_span[qb] = empty ? 0u : (unsigned)(hi - lo);
-    }
+    // key k is visible iff (unsigned)k <= key_span (every key of the history; none if it is empty)
+    const int key_lo = n_kv > 0 ? 0 : 0x3fffffff;
+    const unsigned key_span = n_kv > 0 ? (unsigned)(n_kv - 1) : 0u;
 
     f32x16 oacc[DB][NQB];
 #pragma unroll
@@ -198,18 +169,18 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
 
     // Tiles ahead of the one being consumed are in flight in registers: two (sets A and B,
     // used alternately) for streamed keys when the per-thread share is small enough, else one.
-    constexpr bool PF2 = !WINDOWED && CT::LOADS <= 4;
+    constexpr bool PF2 = CT::LOADS <= 4;
     constexpr int AHEAD = PF2 ? 2 : 1;
     u32x4 kstA[CT::LOADS], vstA[CT::LOADS], kstB[CT::LOADS], vstB[CT::LOADS];
     auto fetch = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt) {
         if (kt < kt_end) {
             const int rows = n_kv - kt * KT;
-            ct.template load<!WINDOWED>(ks, K + kt * tile_bytes, rows);
-            ct.template load<!WINDOWED>(vs, V + kt * tile_bytes, rows);
+            ct.template load<true>(ks, K + kt * tile_bytes, rows);
+            ct.template load<true>(vs, V + kt * tile_bytes, rows);
         }
     };
     auto compute = [&](const char* ldsK, const char* ldsV, int kt) {
-        if (!wave_active || kt < w_begin || kt >= w_end) return;
+        if (!wave_active) return;
         // ---- S^T = K Q^T
         f32x16 sacc[NQB];
 #pragma unroll
@@ -224,19 +195,12 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         }
         // ---- score function, masking, packing
         const int key_base = kt * KT;
-        bool need_mask = key_base + KT > n_kv;
-        if (WINDOWED) {
-            // interior tile: every (valid query, key) pair of the tile is inside the window
-            const int tq_lo = (int)t0, tq_hi = (int)t0 + nq - 1;
-            if (p.left >= 0 && key_base < tq_hi - p.left) need_mask = true;
-            if (p.right >= 0 && key_base + KT - 1 > tq_lo + p.right) need_mask = true;
-        }
+        const bool need_mask = key_base + KT > n_kv;  // only the last tile of a history has invisible keys
         bf16x8 pf[NQB][2];
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            const unsigned rel0 = (unsigned)(key_base + 4 * g - key_lo[qb]);
-            score_to_weights<ACT, DB, NQB>(sacc[qb], need_mask, rel0, key_span[qb], sc, m_ref[qb], l_run[qb], oacc, qb, pf[qb]);
-        }
+        for (int qb = 0; qb < NQB; ++qb)
+            score_to_weights<ACT, DB, NQB>(sacc[qb], need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref[qb],
+                                           l_run[qb], oacc, qb, pf[qb]);
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
@@ -261,9 +225,9 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
         fetch(ks, vs, kt + AHEAD);
         compute(ldsK, ldsV, kt);
     };
-    fetch(kstA, vstA, kt_begin);
-    if (PF2) fetch(kstB, vstB, kt_begin + 1);
-    for (int kt = kt_begin; kt < kt_end; kt += 2) {
+    fetch(kstA, vstA, 0);
+    if (PF2) fetch(kstB, vstB, 1);
+    for (int kt = 0; kt < kt_end; kt += 2) {
         step(kstA, vstA, kt, 0);
         if (kt + 1 < kt_end) {
             if (PF2) step(kstB, vstB, kt + 1, 1);
@@ -311,20 +275,16 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     }
 }
 
-template <int D, int NQB, int NW, bool WINDOWED>
+template <int D, int NQB, int NW>
 __device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds, int act, int h, int64_t q_row0,
-                                                  int nq, int64_t t0, int64_t k0, int n_kv) {
-    if (WINDOWED) {
-        attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX, true>(p, lds, h, q_row0, nq, t0, k0, n_kv);
-    } else {
-        switch (act) {
-        case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_IDENTITY, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU, false>(p, lds, h, q_row0, nq, t0, k0, n_kv); break;
-        }
+                                                  int nq, int64_t k0, int n_kv) {
+    switch (act) {
+    case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_IDENTITY>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU>(p, lds, h, q_row0, nq, k0, n_kv); break;
     }
 }
 
@@ -353,7 +313,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
     const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
-    attn_fwd_dispatch<D, NQB, NW, false>(p, lds, p.head_act[h], h, qb0 + q_first, nq, q_first, k0, n_kv);
+    attn_fwd_dispatch<D, NQB, NW>(p, lds, p.head_act[h], h, qb0 + q_first, nq, k0, n_kv);
 }
 
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
