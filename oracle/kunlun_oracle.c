@@ -19,6 +19,11 @@
  *       Attention": query t sees keys in [t-left, t+right], clipped to its own
  *       sequence; softmax over that set.
  *   - backward: the analytic gradient of <O, dO> with respect to Q, K, V.
+ *   - SumKronLinear          : Eq. (SumKronLinear) in Sec. "Hierarchical Seed
+ *       Pooling", stage 3 (and the last line of Alg. "Hierarchical Seed Pooling"):
+ *           Y_b = sum_{i=1..k} Z_i^T X_b W_i ,  Z_i [S, T], W_i [D, D], X_b [S, D]
+ *       written as the quadruple sum over (i, s, c) per output element, and the
+ *       analytic gradient of <Y, dY> with respect to X, Z, W.
  *
  * Layout ("THD"): Q [total_q, H, d], K and V [total_kv, H, d], O like Q, all
  * row-major doubles; LSE [H, total_q].  Example b owns query rows
@@ -288,6 +293,92 @@ int oracle_swa_bwd(const double* q, const double* k, const double* v, const doub
                    double scale) {
     return attention_backward(q, k, v, d_o, dq, dk, dv, off, off, B, H, d, 0, total, total, scale, ACT_SOFTMAX, NULL,
                               1, left, right);
+}
+
+/*
+ * SumKronLinear, Eq. (SumKronLinear):  Y[b, t, e] = sum_i sum_s sum_c Z[i, s, t] * X[b, s, c] * W[i, c, e].
+ * x [B, S, D], z [k, S, T], w [k, D, D], y [B, T, D], row-major doubles.  The sum is taken exactly
+ * as written, one output element at a time (no intermediate Z^T X, no reordering).
+ */
+int oracle_sumkron_fwd(const double* x, const double* z, const double* w, double* y, int B, int S, int T, int D,
+                       int k) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0) return -1;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t)
+            for (int e = 0; e < D; ++e) {
+                double acc = 0.0;
+                for (int i = 0; i < k; ++i)
+                    for (int s = 0; s < S; ++s) {
+                        const double zst = z[((int64_t)i * S + s) * T + t];
+                        const double* xr = x + ((int64_t)b * S + s) * D;
+                        const double* wc = w + (int64_t)i * D * D + e;
+                        double inner = 0.0;
+                        for (int c = 0; c < D; ++c) inner += xr[c] * wc[(int64_t)c * D];
+                        acc += zst * inner;
+                    }
+                y[((int64_t)b * T + t) * D + e] = acc;
+            }
+    return 0;
+}
+
+/*
+ * Gradient of <Y, dY> of the above:
+ *   dX[b, s, c] = sum_i sum_t sum_e Z[i, s, t] * dY[b, t, e] * W[i, c, e]
+ *   dZ[i, s, t] = sum_b sum_c sum_e X[b, s, c] * W[i, c, e] * dY[b, t, e]
+ *   dW[i, c, e] = sum_b sum_s sum_t X[b, s, c] * Z[i, s, t] * dY[b, t, e]
+ * each written out per output element.
+ */
+int oracle_sumkron_bwd(const double* x, const double* z, const double* w, const double* dy, double* dx, double* dz,
+                       double* dw, int B, int S, int T, int D, int k) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0) return -1;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int s = 0; s < S; ++s)
+            for (int c = 0; c < D; ++c) {
+                double acc = 0.0;
+                for (int i = 0; i < k; ++i)
+                    for (int t = 0; t < T; ++t) {
+                        const double* dyr = dy + ((int64_t)b * T + t) * D;
+                        const double* wr = w + ((int64_t)i * D + c) * D;
+                        double inner = 0.0;
+                        for (int e = 0; e < D; ++e) inner += dyr[e] * wr[e];
+                        acc += z[((int64_t)i * S + s) * T + t] * inner;
+                    }
+                dx[((int64_t)b * S + s) * D + c] = acc;
+            }
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int i = 0; i < k; ++i)
+        for (int s = 0; s < S; ++s)
+            for (int t = 0; t < T; ++t) {
+                double acc = 0.0;
+                for (int b = 0; b < B; ++b) {
+                    const double* xr = x + ((int64_t)b * S + s) * D;
+                    const double* dyr = dy + ((int64_t)b * T + t) * D;
+                    for (int c = 0; c < D; ++c) {
+                        const double* wr = w + ((int64_t)i * D + c) * D;
+                        double inner = 0.0;
+                        for (int e = 0; e < D; ++e) inner += wr[e] * dyr[e];
+                        acc += xr[c] * inner;
+                    }
+                }
+                dz[((int64_t)i * S + s) * T + t] = acc;
+            }
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int i = 0; i < k; ++i)
+        for (int c = 0; c < D; ++c)
+            for (int e = 0; e < D; ++e) {
+                double acc = 0.0;
+                for (int b = 0; b < B; ++b)
+                    for (int s = 0; s < S; ++s) {
+                        const double xv = x[((int64_t)b * S + s) * D + c];
+                        double inner = 0.0;
+                        for (int t = 0; t < T; ++t) inner += z[((int64_t)i * S + s) * T + t] * dy[((int64_t)b * T + t) * D + e];
+                        acc += xv * inner;
+                    }
+                dw[((int64_t)i * D + c) * D + e] = acc;
+            }
+    return 0;
 }
 
 double oracle_act_value(int act, double x) { return act_value(act, x); }

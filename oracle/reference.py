@@ -47,6 +47,8 @@ class OracleLib:
                                        ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
         lib.oracle_swa_bwd.argtypes = [_dp, _dp, _dp, _dp, _dp, _dp, _dp, _ip, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double]
+        lib.oracle_sumkron_fwd.argtypes = [_dp, _dp, _dp, _dp] + [ctypes.c_int] * 5
+        lib.oracle_sumkron_bwd.argtypes = [_dp] * 7 + [ctypes.c_int] * 5
         lib.oracle_act_value.argtypes = [ctypes.c_int, ctypes.c_double]
         lib.oracle_act_value.restype = ctypes.c_double
         lib.oracle_act_deriv.argtypes = [ctypes.c_int, ctypes.c_double]
@@ -120,6 +122,28 @@ class OracleLib:
                                  d, q.shape[0], int(left), int(right), float(scale))
         return dq, dk, dv
 
+    def sumkron_fwd(self, x, z, w):
+        """SumKronLinear: x [B,S,D], z [k,S,T], w [k,D,D] -> y [B,T,D]."""
+        x, z, w = _f64(x), _f64(z), _f64(w)
+        B, S, D = x.shape
+        k, S2, T = z.shape
+        assert S2 == S and w.shape == (k, D, D)
+        y = np.zeros((B, T, D), dtype=np.float64)
+        rc = self._lib.oracle_sumkron_fwd(_p(x), _p(z), _p(w), _p(y), B, S, T, D, k)
+        assert rc == 0
+        return y
+
+    def sumkron_bwd(self, x, z, w, dy):
+        """Gradient of <Y, dY> with respect to x, z, w.  Returns (dx, dz, dw)."""
+        x, z, w, dy = _f64(x), _f64(z), _f64(w), _f64(dy)
+        B, S, D = x.shape
+        k, S2, T = z.shape
+        assert S2 == S and w.shape == (k, D, D) and dy.shape == (B, T, D)
+        dx, dz, dw = np.zeros_like(x), np.zeros_like(z), np.zeros_like(w)
+        rc = self._lib.oracle_sumkron_bwd(_p(x), _p(z), _p(w), _p(dy), _p(dx), _p(dz), _p(dw), B, S, T, D, k)
+        assert rc == 0
+        return dx, dz, dw
+
     def act_value(self, act, x):
         return self._lib.oracle_act_value(int(act), float(x))
 
@@ -135,6 +159,8 @@ gdpa_fwd = _default.gdpa_fwd
 gdpa_bwd = _default.gdpa_bwd
 swa_fwd = _default.swa_fwd
 swa_bwd = _default.swa_bwd
+sumkron_fwd = _default.sumkron_fwd
+sumkron_bwd = _default.sumkron_bwd
 act_value = _default.act_value
 act_deriv = _default.act_deriv
 num_threads = _default.num_threads

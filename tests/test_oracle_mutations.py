@@ -7,6 +7,7 @@ import subprocess
 import pytest
 
 from tests import test_oracle_pins as pins
+from tests import test_oracle_sumkron_pins as kpins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "kunlun_oracle.c")
@@ -32,6 +33,22 @@ MUTANTS = [
     ("dk_uses_keys", "dk[krow + c] += ds * q[qrow + c];", "dk[krow + c] += ds * k[krow + c];", 0),
     ("dv_uses_ds", "dv[krow + c] += p[j] * d_o[qrow + c];", "dv[krow + c] += ds * d_o[qrow + c];", 0),
     ("dp_uses_keys", "dpj += d_o[qrow + c] * v[krow + c];", "dpj += d_o[qrow + c] * k[krow + c];", 0),
+    # SumKronLinear
+    ("sumkron_z_not_transposed", "const double zst = z[((int64_t)i * S + s) * T + t];",
+     "const double zst = z[((int64_t)i * S + (s % T)) * T + (t % S)];", 0),
+    ("sumkron_w_transposed", "const double* wc = w + (int64_t)i * D * D + e;\n                        double inner = 0.0;\n"
+     "                        for (int c = 0; c < D; ++c) inner += xr[c] * wc[(int64_t)c * D];",
+     "const double* wc = w + (int64_t)i * D * D + (int64_t)e * D;\n                        double inner = 0.0;\n"
+     "                        for (int c = 0; c < D; ++c) inner += xr[c] * wc[c];", 0),
+    ("sumkron_weight_of_first_term_only", "const double* wc = w + (int64_t)i * D * D + e;", "const double* wc = w + e;", 0),
+    ("sumkron_dx_uses_w_transposed", "const double* wr = w + ((int64_t)i * D + c) * D;\n                        double inner = 0.0;\n"
+     "                        for (int e = 0; e < D; ++e) inner += dyr[e] * wr[e];",
+     "const double* wr = w + (int64_t)i * D * D + c;\n                        double inner = 0.0;\n"
+     "                        for (int e = 0; e < D; ++e) inner += dyr[e] * wr[(int64_t)e * D];", 0),
+    ("sumkron_dz_drops_batch_sum", "for (int b = 0; b < B; ++b) {\n                    const double* xr = x + ((int64_t)b * S + s) * D;",
+     "for (int b = 0; b < 1; ++b) {\n                    const double* xr = x + ((int64_t)b * S + s) * D;", 0),
+    ("sumkron_dw_uses_wrong_z_term", "inner += z[((int64_t)i * S + s) * T + t] * dy[((int64_t)b * T + t) * D + e];",
+     "inner += z[((int64_t)0 * S + s) * T + t] * dy[((int64_t)b * T + t) * D + e];", 0),
 ]
 
 
@@ -59,6 +76,12 @@ def _battery():
     for act in ("softmax", "gelu"):
         calls.append((pins.test_gdpa_backward_finite_differences, dict(act=act)))
     calls.append((pins.test_swa_backward_finite_differences, dict(window=(2, 0))))
+    calls.append((kpins.test_sumkron_hand_worked, {}))
+    calls.append((kpins.test_sumkron_equals_explicit_kronecker_matrix, {}))
+    calls.append((kpins.test_sumkron_single_entry_probes, {}))
+    calls.append((kpins.test_sumkron_selection_and_separable_cases, {}))
+    calls.append((kpins.test_sumkron_backward_finite_differences, {}))
+    calls.append((kpins.test_sumkron_backward_vs_autograd, {}))
     return calls
 
 
