@@ -241,6 +241,20 @@ def main():
         other["pffn_direction_gdpa_bwd"] = entry(*t, 3 * w3.total_kv * elt + 4 * w3.B * n_ctx * elt,
                                                  10.0 * w3.d * w3.H * n_ctx * w3.total_kv)
 
+        # SumKronLinear (stage 3 of hierarchical seed pooling) at the paper's typical configuration:
+        # matrix-core-bound (about 570 flop per byte of X).
+        Bk, Sk, Tk, Dk, kk = 1024, 256, 32, 384, 8
+        xk = device_normal(torch, (Bk, Sk, Dk), 1.0, 41)
+        zk = device_normal(torch, (kk, Sk, Tk), 1.0 / math.sqrt(Sk), 42)
+        wk = device_normal(torch, (kk, Dk, Dk), 1.0 / math.sqrt(Dk), 43)
+        yk = torch.empty((Bk, Tk, Dk), dtype=torch.bfloat16, device="cuda")
+        wsk = torch.empty(kb.sumkron_workspace_bytes(Bk, Sk, Tk, Dk, kk), dtype=torch.uint8, device="cuda")
+        tw, tc = timed(lambda: kb.sumkron_fwd(xk, zk, wk, out=yk, workspace=wsk), n=10)
+        fl = 2.0 * Bk * kk * Tk * Dk * (Sk + Dk)
+        other["sumkron_fwd_S256_T32_D384_k8_B1024"] = {"us": round(tc, 1), "us_warm": round(tw, 1), "tflops": round(fl / tc / 1e6, 1),
+                                                       "pct_mfma_peak": round(100 * fl / (tc * 1e-6) / MFMA_BF16_PEAK, 2)}
+        del xk, yk, wsk
+
         # Diagnostic, not a workload of the paper: the same forward entry point on a shape that IS
         # matrix-core-bound (512 queries per example: 512 flop per K/V byte, above the ridge), to show
         # what the MFMA pipeline of these kernels sustains when HBM is out of the way.

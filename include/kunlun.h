@@ -20,6 +20,9 @@
  *                    Window Attention": query t attends to keys [t-left, t+right] of its
  *                    own sequence under softmax.
  *   kunlun_swa_bwd   Gradient of <O, dO> of the same with respect to Q, K, V.
+ *   kunlun_sumkron_fwd  SumKronLinear, Eq. (SumKronLinear) of Sec. "Hierarchical Seed Pooling"
+ *                    (stage 3: compression of the S pooled seeds to T tokens):
+ *                        Y_b = sum_{i=1..k} Z_i^T X_b W_i .
  *
  * Jagged layout.  A batch holds B examples.  Tensors are packed "tokens, heads, channels":
  *   Q  [total_q,  H, d]      O, dO, dQ like Q
@@ -149,6 +152,24 @@ int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, c
  * max_kv and total as total_q and total_kv. */
 size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
                               int64_t total_kv);
+
+/*
+ * SumKronLinear forward (Eq. (SumKronLinear)):  Y[b] = sum_i Z[i]^T X[b] W[i].
+ *   x  in,  device, [B, S, D]   the S pooled seed vectors of every example
+ *   z  in,  device, [k, S, T]   sequence-side factors Z_i
+ *   w  in,  device, [k, D, D]   embedding-side factors W_i (applied from the right: rows = input channel)
+ *   y  out, device, [B, T, D]   fully overwritten
+ * all row-major, contiguous, `dtype` elements, 16-byte aligned.  KUNLUN_BF16: both contractions on
+ * the matrix cores with fp32 accumulation when D is a multiple of 128 and S a multiple of 32 (the
+ * intermediate Z_i^T X_b is rounded to bf16 once); other shapes and KUNLUN_FP32 take plain fp32
+ * kernels.  workspace: device, at least kunlun_sumkron_workspace_bytes(...) bytes, 256-byte aligned.
+ * B == 0 is legal and does nothing.  Errors as for the other entry points.
+ */
+int kunlun_sumkron_fwd(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
+                       int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace that kunlun_sumkron_fwd needs for these sizes (0 for invalid sizes). */
+size_t kunlun_sumkron_workspace_bytes(int B, int S, int T, int D, int k, int dtype);
 
 /* Static, human-readable text for a kunlun_status. */
 const char* kunlun_strerror(int status);

@@ -22,7 +22,7 @@ BF16, FP32 = 0, 1
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
-           "kunlun_strerror"]
+           "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -38,6 +38,10 @@ _lib.kunlun_swa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp
 _lib.kunlun_swa_bwd.restype = _i
 _lib.kunlun_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i, _i64, _i64]
 _lib.kunlun_workspace_bytes.restype = _sz
+_lib.kunlun_sumkron_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.kunlun_sumkron_fwd.restype = _i
+_lib.kunlun_sumkron_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
+_lib.kunlun_sumkron_workspace_bytes.restype = _sz
 _lib.kunlun_strerror.argtypes = [_i]
 _lib.kunlun_strerror.restype = ctypes.c_char_p
 
@@ -164,3 +168,20 @@ def swa_bwd(q, k, v, o, lse, d_o, offsets, window_left, window_right, scale, *, 
     if rc != OK:
         raise KunlunError(rc)
     return dq, dk, dv
+
+
+def sumkron_workspace_bytes(B, S, T, D, k, dtype=BF16) -> int:
+    return int(_lib.kunlun_sumkron_workspace_bytes(B, S, T, D, k, dtype))
+
+
+def sumkron_fwd(x, z, w, *, out=None, workspace=None, stream=None):
+    """kunlun_sumkron_fwd.  x [B,S,D], z [k,S,T], w [k,D,D] device tensors; returns y [B,T,D]."""
+    B, S, D = x.shape
+    k, _, T = z.shape
+    y = torch.empty((B, T, D), dtype=x.dtype, device=x.device) if out is None else out
+    ws = _workspace(workspace, sumkron_workspace_bytes(B, S, T, D, k, _dtype_code(x)), x.device)
+    rc = _lib.kunlun_sumkron_fwd(_ptr(x), _ptr(z), _ptr(w), _ptr(y), B, S, T, D, k, _dtype_code(x), _ptr(ws), ws.numel(),
+                                 _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return y

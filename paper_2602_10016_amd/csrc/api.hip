@@ -57,6 +57,26 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
     }
 }
 
+size_t kunlun_sumkron_workspace_bytes(int B, int S, int T, int D, int k, int dtype) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0 || (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32)) return 0;
+    return sumkron_workspace(B, S, T, D, k, dtype) + 256;
+}
+
+int kunlun_sumkron_fwd(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
+                       int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0) return KUNLUN_ERR_SHAPE;
+    if (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32) return KUNLUN_ERR_UNSUPPORTED;
+    // 32-bit index arithmetic inside a row block of the kernels
+    if ((int64_t)k * D > (1 << 20) || (int64_t)k * T > (1 << 20) || S > (1 << 20) || D % 8 != 0) return KUNLUN_ERR_UNSUPPORTED;
+    if (B == 0) return KUNLUN_OK;
+    if (!x || !z || !w || !y) return KUNLUN_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(z, 16) || !aligned(w, 16) || !aligned(y, 16)) return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kunlun_sumkron_workspace_bytes(B, S, T, D, k, dtype)) return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+    const hipError_t e = launch_sumkron(x, z, w, y, B, S, T, D, k, dtype, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
 const char* kunlun_strerror(int status) {
     switch (status) {
     case KUNLUN_OK: return "ok";

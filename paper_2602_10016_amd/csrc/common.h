@@ -59,6 +59,11 @@ bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype);
 size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv);
 hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool any_softmax, hipStream_t stream);
 
+// SumKronLinear (two tiled GEMMs with a bf16 intermediate, or plain fp32 kernels)
+size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype);
+hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
+                          int dtype, void* workspace, hipStream_t stream);
+
 #ifdef __HIPCC__
 // ---- device helpers ----
 

@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 6
+    assert len(declared) == 8
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
@@ -108,3 +108,19 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_sumkron_argument_validation_without_gpu(kb):
+    lib = kb.raw()
+    call = lambda x=0x1000, z=0x1000, w=0x1000, y=0x1000, B=2, S=32, T=4, D=128, k=2, dtype=kb.BF16, ws=0x1000, n=1 << 30: \
+        lib.kunlun_sumkron_fwd(x, z, w, y, B, S, T, D, k, dtype, ws, n, None)
+    assert call(S=0) == kb.ERR_SHAPE and call(k=0) == kb.ERR_SHAPE and call(B=-1) == kb.ERR_SHAPE
+    assert call(dtype=7) == kb.ERR_UNSUPPORTED
+    assert call(D=12) == kb.ERR_UNSUPPORTED
+    assert call(B=0) == kb.OK  # nothing to do, nothing launched
+    assert call(x=None) == kb.ERR_NULL and call(y=None) == kb.ERR_NULL
+    assert call(z=0x1004) == kb.ERR_ALIGN
+    assert call(ws=None) == kb.ERR_WORKSPACE and call(n=16) == kb.ERR_WORKSPACE
+    assert call(ws=0x1010) == kb.ERR_ALIGN
+    need = kb.sumkron_workspace_bytes(1024, 256, 32, 384, 8)
+    assert need >= 1024 * 32 * 8 * 384 * 2 and kb.sumkron_workspace_bytes(4, 0, 1, 8, 1) == 0

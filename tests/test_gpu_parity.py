@@ -366,6 +366,51 @@ def test_backward_per_head_activations(kb, oracle):
     check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
 
 
+# ---------------- SumKronLinear ----------------
+
+def _sumkron_inputs(seed, B, S, T, D, k, dtype):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, S, D), dtype=np.float32)
+    z = rng.standard_normal((k, S, T), dtype=np.float32) / math.sqrt(S)
+    w = rng.standard_normal((k, D, D), dtype=np.float32) / math.sqrt(D)
+    if dtype == "bf16":
+        x, z, w = W.round_to_bf16(x), W.round_to_bf16(z), W.round_to_bf16(w)
+    return x, z, w
+
+
+@pytest.mark.parametrize("B,S,T,D,k", [(5, 256, 32, 384, 8),     # the paper's typical configuration
+                                       (3, 64, 32, 128, 2),      # one tile in every direction
+                                       (7, 96, 20, 256, 3),      # k*T = 60 and B*T = 140: ragged row tiles
+                                       (2, 32, 1, 128, 1),       # a single output token, a single term
+                                       (1, 160, 48, 512, 5)])
+def test_sumkron_forward_tiled(kb, oracle, B, S, T, D, k):
+    """bf16 matrix-core path (two tiled GEMMs).  The intermediate Z^T X (sums of S products of
+    magnitude 1/sqrt(S), so O(1)) is rounded to bf16 once: relative 2^-9 per term of the second sum."""
+    x, z, w = _sumkron_inputs(50 + B, B, S, T, D, k, "bf16")
+    y = kb.sumkron_fwd(to_dev(x, "bf16"), to_dev(z, "bf16"), to_dev(w, "bf16"))
+    torch.cuda.synchronize()
+    assert_close(to_np(y), oracle.sumkron_fwd(x, z, w), TOL["bf16"], f"sumkron B={B} S={S} T={T} D={D} k={k}")
+
+
+@pytest.mark.parametrize("dtype,B,S,T,D,k", [("fp32", 3, 40, 6, 24, 3), ("bf16", 2, 24, 5, 40, 2), ("fp32", 2, 64, 32, 128, 2)])
+def test_sumkron_forward_plain_kernels(kb, oracle, dtype, B, S, T, D, k):
+    x, z, w = _sumkron_inputs(60, B, S, T, D, k, dtype)
+    y = kb.sumkron_fwd(to_dev(x, dtype), to_dev(z, dtype), to_dev(w, dtype))
+    torch.cuda.synchronize()
+    assert_close(to_np(y), oracle.sumkron_fwd(x, z, w), TOL[dtype] if dtype == "bf16" else 2e-5, f"sumkron plain {dtype}")
+
+
+def test_sumkron_examples_are_isolated_and_repeatable(kb):
+    x, z, w = _sumkron_inputs(61, 6, 64, 32, 128, 2, "bf16")
+    xd, zd, wd = to_dev(x, "bf16"), to_dev(z, "bf16"), to_dev(w, "bf16")
+    y1 = kb.sumkron_fwd(xd, zd, wd)
+    y2 = kb.sumkron_fwd(xd, zd, wd)
+    y3 = kb.sumkron_fwd(xd[2:5].contiguous(), zd, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+    assert torch.equal(y1[2:5], y3)
+
+
 # ---------------- HIP graph capture ----------------
 
 def test_graph_capture_replays_match_eager(kb):
