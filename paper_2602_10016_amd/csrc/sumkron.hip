@@ -7,7 +7,7 @@
 //                            = rows (i, t) of  Zt [k*T, S] * X_b [S, D],  Zt = all Z_i transposed
 //     stage 2, whole batch:  Y [B*T, D] = U [B*T, k*D] * Wcat [k*D, D],   Wcat = the W_i stacked
 // Both run the same kernel: C = A * B for row-major bf16 operands, fp32 accumulation,
-// 128 x 128 output tiles, K in steps of 32 through a ring of three LDS stages filled by
+// 256 x 128 (or 128 x 128) output tiles, K in steps of 32 through a ring of three LDS stages filled by
 // buffer-load-to-LDS (lds_ring.h).  The kernel computes the transposed tile C^T = B^T A^T: B^T
 // fragments come from the row-major B tile through transposing LDS reads, A^T fragments are
 // plain row reads of the A tile, and every lane ends up owning one row of C with consecutive
@@ -17,7 +17,7 @@
 
 namespace kunlun {
 
-constexpr int GM = 128, GN = 128, GK = 32;  // output tile and K step
+constexpr int GN = 128, GK = 32;  // output tile columns and K step; tile rows = 64 * MB (template)
 
 struct GemmArgs {
     const bf16_t* a;      // [batch][M, K], row stride lda
@@ -31,20 +31,25 @@ struct GemmArgs {
     int unit_is_batch;    // 1: unit = batch (tiles = m_tiles*n_tiles), 0: unit = m tile (tiles = n_tiles)
 };
 
+template <int MB>  // 32-row blocks per wave: the workgroup tile has 64*MB rows (2 x 2 waves)
 struct GemmSmem {
-    static constexpr int A_TILE = GM * GK * 2;  // 128 rows x 64 bytes, chunk ^= (row / 4) % 4
+    static constexpr int GM = 64 * MB;
+    static constexpr int A_TILE = GM * GK * 2;  // GM rows x 64 bytes, chunk ^= (row / 4) % 4
     static constexpr int B_TILE = GK * GN * 2;  // 32 rows x 256 bytes, V swizzle of TileLayout<128>
     static constexpr int STAGE = A_TILE + B_TILE;
     static constexpr int TOTAL = 3 * STAGE;
-    static constexpr int OUT_STRIDE = 64 * 2 + 16;  // a wave's 64 x 64 bf16 output block, padded rows
+    static constexpr int OUT_STRIDE = 64 * 2 + 16;  // a wave's output block goes out 64 rows x 64 columns at a time, padded rows
     static_assert(4 * 64 * OUT_STRIDE <= TOTAL, "output staging must fit");
 };
 
 __device__ __forceinline__ int a_tile_offset(int row, int chunk) { return row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4); }
 
+template <int MB>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
-    __shared__ __attribute__((aligned(1024))) char lds[GemmSmem::TOTAL];
-    using SM = GemmSmem;
+    using SM = GemmSmem<MB>;
+    constexpr int GM = SM::GM;
+    constexpr int A_LOADS = GM / 64;  // A-tile load instructions (16 rows each) per wave
+    __shared__ __attribute__((aligned(1024))) char lds[SM::TOTAL];
     using L = TileLayout<128>;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -69,11 +74,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
     const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
     const uint32_t lds0 = lds_address(lds);
 
-    // ---- tile transport: A tile 8 load instructions (16 rows each), B tile 8 (4 rows each); 2 + 2 per wave
-    uint32_t a_voff[2];
+    // ---- tile transport: A tile GM/16 load instructions (16 rows each), B tile 8 (4 rows each), split over the waves
+    uint32_t a_voff[A_LOADS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = (wave * 2 + i) * 16 + lane / 4, pos = lane % 4;
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int row = (wave * A_LOADS + i) * 16 + lane / 4, pos = lane % 4;
         const int src_row = row < rows_valid ? row : rows_valid - 1;  // rows past M re-read the last one (never stored)
         a_voff[i] = (uint32_t)src_row * lda_b + ((pos ^ ((row >> 2) & 3)) << 4);
     }
@@ -83,15 +88,16 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
     auto issue = [&](int ks, int stage) {
         const uint32_t dst = lds0 + stage * SM::STAGE;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) load_to_lds_b128(a_rsrc, a_voff[i], (uint32_t)ks * (GK * 2), dst + (wave * 2 + i) * 1024);
+        for (int i = 0; i < A_LOADS; ++i)
+            load_to_lds_b128(a_rsrc, a_voff[i], (uint32_t)ks * (GK * 2), dst + (wave * A_LOADS + i) * 1024);
         bdma.issue(B + (int64_t)ks * GK * ldb_b, GK, dst + SM::A_TILE);
     };
-    constexpr int LOADS_PER_STEP = 2 + TileDma<128, 4, SWZ_V>::IPW;
+    constexpr int LOADS_PER_STEP = A_LOADS + TileDma<128, 4, SWZ_V>::IPW;
     const int n_steps = p.K / GK;
     issue(0, 0);
     if (n_steps > 1) issue(1, 1);
 
-    // ---- wave (wm, wn) owns the 64 x 64 block at rows 64*wm, columns 64*wn of the tile
+    // ---- wave (wm, wn) owns the (32*MB) x 64 block at rows 32*MB*wm, columns 64*wn of the tile
     const int wm = wave >> 1, wn = wave & 1;
     // B^T fragment (A operand: row = column n of C, contraction k = 16c + 8g + 0..7): two transposing reads
     const int s16 = lane & 15, hi16 = (lane >> 4) & 1;
@@ -100,15 +106,14 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
     for (int half = 0; half < 2; ++half)
         bt_rd[half] = SM::A_TILE + L::v_offset(8 * g + 4 * half + (s16 >> 2), (64 * wn + 16 * hi16 + 4 * (s16 & 3)) * 2);
     // A^T fragment (B operand: column = row m of C, contraction k = 16c + 8g + 0..7): one 16-byte read of row m
-    int a_rd[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) a_rd[mb] = a_tile_offset(64 * wm + 32 * mb + r, g);  // ^ (c << 5) for k step c
+    // (rows 32 apart share the swizzle: + 32*64 bytes per block mb; ^ (c << 5) for k step c)
+    const int a_rd = a_tile_offset(32 * MB * wm + r, g);
 
-    f32x16 acc[2][2];  // [nb][mb]
+    f32x16 acc[2][MB];  // [nb][mb]
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
@@ -122,9 +127,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
         stage = stage == 2 ? 0 : stage + 1;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            bf16x8 af[2], bf[2];
+            bf16x8 af[MB], bf[2];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) af[mb] = *(const bf16x8*)(st + (a_rd[mb] ^ (c << 5)));
+            for (int mb = 0; mb < MB; ++mb) af[mb] = *(const bf16x8*)(st + mb * 32 * 64 + (a_rd ^ (c << 5)));
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
                 // column block nb of the wave = 64-byte group 2*wn + nb of the B tile row: XOR on bit 6
@@ -137,32 +142,36 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(GemmArgs p) {
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb) acc[nb][mb] = mfma32(bf[nb], af[mb], acc[nb][mb]);
+                for (int mb = 0; mb < MB; ++mb) acc[nb][mb] = mfma32(bf[nb], af[mb], acc[nb][mb]);
         }
     }
 
-    // ---- epilogue: lane holds row m = 64*wm + 32*mb + r, columns 64*wn + 32*nb + 8*(v/4) + 4g + (v%4)
+    // ---- epilogue: lane holds row m = 32*MB*wm + 32*mb + r, columns 64*wn + 32*nb + 8*(v/4) + 4g + (v%4);
+    // 64 rows of the wave's block at a time through its own padded staging rows, whole rows out
     __syncthreads();  // every wave is done with the ring
     char* out = lds + wave * (64 * SM::OUT_STRIDE);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                bf16x4 o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)acc[nb][mb][4 * vg + e];
-                *(bf16x4*)(out + (32 * mb + r) * SM::OUT_STRIDE + (32 * nb + 8 * vg + 4 * g) * 2) = o4;
-            }
-    // whole rows out: 8 lanes x 16 bytes per row of the wave's block, 8 rows per pass
     bf16_t* cb = p.c + batch * p.c_batch + n0 + 64 * wn;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = i * 8 + lane / 8, ch = lane % 8;
-        const int m = m0 + 64 * wm + row;
-        const u32x4 val = *(const u32x4*)(out + row * SM::OUT_STRIDE + ch * 16);
-        if (m < p.M) *(u32x4*)(cb + (int64_t)(m % p.c_mod) * p.c_lo + (int64_t)(m / p.c_mod) * p.c_hi + ch * 8) = val;
+    for (int half = 0; half < MB / 2; ++half) {
+#pragma unroll
+        for (int mb2 = 0; mb2 < 2; ++mb2)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = (bf16_t)acc[nb][2 * half + mb2][4 * vg + e];
+                    *(bf16x4*)(out + (32 * mb2 + r) * SM::OUT_STRIDE + (32 * nb + 8 * vg + 4 * g) * 2) = o4;
+                }
+        // 8 lanes x 16 bytes per row, 8 rows per pass (the staging rows are private to the wave)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = i * 8 + lane / 8, ch = lane % 8;
+            const int m = m0 + 32 * MB * wm + 64 * half + row;
+            const u32x4 val = *(const u32x4*)(out + row * SM::OUT_STRIDE + ch * 16);
+            if (m < p.M) *(u32x4*)(cb + (int64_t)(m % p.c_mod) * p.c_lo + (int64_t)(m / p.c_mod) * p.c_hi + ch * 8) = val;
+        }
     }
 }
 
@@ -215,6 +224,17 @@ size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype) {
 
 static unsigned gemm_grid(int64_t units, int tiles_per_unit) { return (unsigned)(((units + 7) / 8) * 8 * tiles_per_unit); }
 
+// 256-row tiles (16 MFMAs per wave between two barriers) when the rows fill them, else 128-row tiles
+static void launch_gemm(GemmArgs g, hipStream_t stream) {
+    const bool tall = g.M % 256 == 0 || g.M >= 1024;
+    const int gm = tall ? 256 : 128;
+    g.m_tiles = (g.M + gm - 1) / gm;
+    g.tiles_per_unit = g.unit_is_batch ? g.m_tiles * g.n_tiles : g.n_tiles;
+    const unsigned grid = gemm_grid(g.unit_is_batch ? g.batches : g.m_tiles, g.tiles_per_unit);
+    if (tall) hipLaunchKernelGGL(gemm_bf16_kernel<4>, dim3(grid), dim3(256), 0, stream, g);
+    else hipLaunchKernelGGL(gemm_bf16_kernel<2>, dim3(grid), dim3(256), 0, stream, g);
+}
+
 hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
                           int dtype, void* workspace, hipStream_t stream) {
     if (sumkron_tiled_supported(S, T, D, k, dtype)) {
@@ -228,17 +248,15 @@ hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, 
         g1.b = (const bf16_t*)x; g1.b_batch = (int64_t)S * D; g1.ldb = D;
         g1.c = u; g1.c_batch = (int64_t)T * k * D; g1.c_mod = T; g1.c_lo = (int64_t)k * D; g1.c_hi = D;
         g1.M = k * T; g1.N = D; g1.K = S;
-        g1.m_tiles = (g1.M + GM - 1) / GM; g1.n_tiles = D / GN; g1.batches = B;
-        g1.unit_is_batch = 1; g1.tiles_per_unit = g1.m_tiles * g1.n_tiles;
-        hipLaunchKernelGGL(gemm_bf16_kernel, dim3(gemm_grid(B, g1.tiles_per_unit)), dim3(256), 0, stream, g1);
+        g1.n_tiles = D / GN; g1.batches = B; g1.unit_is_batch = 1;
+        launch_gemm(g1, stream);
         GemmArgs g2 = {};  // Y [B*T, D] = U [B*T, k*D] * Wcat [k*D, D]
         g2.a = u; g2.a_batch = 0; g2.lda = k * D;
         g2.b = (const bf16_t*)w; g2.b_batch = 0; g2.ldb = D;
         g2.c = (bf16_t*)y; g2.c_batch = 0; g2.c_mod = 1; g2.c_lo = 0; g2.c_hi = D;
         g2.M = B * T; g2.N = D; g2.K = k * D;
-        g2.m_tiles = (g2.M + GM - 1) / GM; g2.n_tiles = D / GN; g2.batches = 1;
-        g2.unit_is_batch = 0; g2.tiles_per_unit = g2.n_tiles;
-        hipLaunchKernelGGL(gemm_bf16_kernel, dim3(gemm_grid(g2.m_tiles, g2.tiles_per_unit)), dim3(256), 0, stream, g2);
+        g2.n_tiles = D / GN; g2.batches = 1; g2.unit_is_batch = 0;
+        launch_gemm(g2, stream);
         return hipGetLastError();
     }
     float* u = (float*)workspace;
