@@ -281,6 +281,77 @@ def test_cfg4_full_size_sampled(kb, oracle, act):
     assert torch.isfinite(o.float()).all()
 
 
+@pytest.mark.parametrize("act", ["gelu", "softmax"])
+def test_cfg4_full_size_backward_sampled(kb, oracle, act):
+    """The backward call of the bench step at full size (same launch configuration); the oracle
+    recomputes dQ, dK, dV of sampled (example, head) items."""
+    r = W.CONFIGS["cfg4"]
+    B, H, d, Nq = r["B"], r["H"], r["d"], r["Nq"]
+    lengths = W.make_lengths("cfg4", 0)
+    off = W.offsets_from_lengths(lengths)
+    T = int(off[-1])
+    q = device_normal((B * Nq, H, d), 0.5, 1)
+    k = device_normal((T, H, d), 0.5, 2)
+    v = device_normal((T, H, d), 0.5, 3)
+    d_o = device_normal((B * Nq, H, d), 1.0, 4)
+    scale = 1 / math.sqrt(d) if act == "softmax" else 1.0 / r["tau"]
+    offd = offsets_dev(off)
+    o, lse = kb.gdpa_fwd(q, k, v, offd, scale, ACTS[act], max_q=Nq, max_kv=4096)
+    dq, dk, dv = kb.gdpa_bwd(q, k, v, d_o, offd, scale, ACTS[act], o=o, lse=lse, max_q=Nq, max_kv=4096)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    order = np.argsort(lengths)
+    picks = list(order[:3]) + list(order[-3:]) + list(rng.choice(B, size=10, replace=False))
+    for b in picks:
+        h = int(rng.integers(H))
+        ks = slice(int(off[b]), int(off[b + 1]))
+        qs = slice(b * Nq, (b + 1) * Nq)
+        dq_ref, dk_ref, dv_ref = oracle.gdpa_bwd(to_np(q[qs, h:h + 1]), to_np(k[ks, h:h + 1]), to_np(v[ks, h:h + 1]),
+                                                 to_np(d_o[qs, h:h + 1]), [0, lengths[b]], scale, ACTS[act], max_q=Nq)
+        what = f"cfg4 bwd b={b} h={h} L={lengths[b]}"
+        assert_close(to_np(dq[qs, h:h + 1]), dq_ref, TOL["bf16"], what + " dQ")
+        assert_close(to_np(dk[ks, h:h + 1]), dk_ref, TOL["bf16"], what + " dK")
+        assert_close(to_np(dv[ks, h:h + 1]), dv_ref, TOL["bf16"], what + " dV")
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+
+
+def test_cfg4_full_size_sliding_window_sampled(kb, oracle):
+    """The sliding-window call of the bench step at full size (window of 256 causal keys over the
+    cfg4 batch), forward and backward; the oracle recomputes sampled (sequence, head) items."""
+    r = W.CONFIGS["cfg4"]
+    H, d = r["H"], r["d"]
+    lengths = W.make_lengths("cfg4", 0)
+    off = W.offsets_from_lengths(lengths)
+    T, B = int(off[-1]), len(lengths)
+    q = device_normal((T, H, d), 0.5, 5)
+    k = device_normal((T, H, d), 0.5, 2)
+    v = device_normal((T, H, d), 0.5, 3)
+    d_o = device_normal((T, H, d), 1.0, 6)
+    scale = 1 / math.sqrt(d)
+    offd = offsets_dev(off)
+    o, lse = kb.swa_fwd(q, k, v, offd, 255, 0, scale, max_len=4096)
+    dq, dk, dv = kb.swa_bwd(q, k, v, o, lse, d_o, offd, 255, 0, scale, max_len=4096)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2)
+    order = np.argsort(lengths)
+    picks = list(order[:2]) + [int(order[-1])] + list(rng.choice(B, size=5, replace=False))
+    for b in picks:
+        h = int(rng.integers(H))
+        rows = slice(int(off[b]), int(off[b + 1]))
+        sub = lambda t: to_np(t[rows, h:h + 1])
+        o_ref, lse_ref = oracle.swa_fwd(sub(q), sub(k), sub(v), [0, lengths[b]], 255, 0, scale)
+        what = f"cfg4 swa b={b} h={h} L={lengths[b]}"
+        assert_close(sub(o), o_ref, TOL["bf16"], what + " O")
+        assert_lse_close(to_np(lse[h, rows]), lse_ref[0], 1e-2)
+        dq_ref, dk_ref, dv_ref = oracle.swa_bwd(sub(q), sub(k), sub(v), sub(d_o), [0, lengths[b]], 255, 0, scale)
+        assert_close(sub(dq), dq_ref, TOL["bf16"], what + " dQ")
+        assert_close(sub(dk), dk_ref, TOL["bf16"], what + " dK")
+        assert_close(sub(dv), dv_ref, TOL["bf16"], what + " dV")
+    for t in (o, dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+
+
 # ---------------- config 5: backward ----------------
 
 def check_gdpa_bwd(kb, oracle, wl, act, head_act=None):
