@@ -264,10 +264,13 @@ def main():
         vd = device_normal(torch, (Bd * Ld, H, d), 0.5, 23)
         offd = torch.arange(0, (Bd + 1) * Ld, Ld, dtype=torch.int32, device="cuda")
         od = torch.empty_like(qd)
-        tw, tc = timed(lambda: kb.gdpa_fwd(qd, kd, vd, offd, 1.0 / Ld, act, max_q=Nd, max_kv=Ld, out=od, want_lse=False, workspace=wsx), n=10)
         fl = W.gdpa_flops(H, d, Nd, Bd * Ld)
-        other["diagnostic_mfma_bound_gdpa_fwd_Nq512"] = {"us": round(tw, 1), "tflops": round(fl / tw / 1e6, 1),
-                                                          "pct_mfma_peak": round(100 * fl / (tw * 1e-6) / MFMA_BF16_PEAK, 2)}
+        diag = {}
+        for name, a, sc_ in (("gelu", act, 1.0 / Ld), ("softmax", kb.ACT_SOFTMAX, 1.0 / math.sqrt(d))):
+            tw, _ = timed(lambda: kb.gdpa_fwd(qd, kd, vd, offd, sc_, a, max_q=Nd, max_kv=Ld, out=od, want_lse=False, workspace=wsx), n=10)
+            diag[name] = {"us": round(tw, 1), "tflops": round(fl / tw / 1e6, 1),
+                          "pct_mfma_peak": round(100 * fl / (tw * 1e-6) / MFMA_BF16_PEAK, 2)}
+        other["diagnostic_mfma_bound_gdpa_fwd_Nq512"] = diag
 
         # Measured speed of light of this device, by library routines of the harness (torch): a 1 GiB
         # device-to-device copy (read + write) and a large bf16 GEMM.
