@@ -59,7 +59,7 @@ __device__ __forceinline__ void store_tile_rows(char* stage, const f32x16 (&acc)
     for (int i = 0; i < 32 * CHUNKS / 64; ++i) {
         const int row = i * (64 / CHUNKS) + rsub;
         const u32x4 val = *(const u32x4*)(stage + row * PT::ROW_STRIDE + chunk * 16);
-        if (row < n_rows) *(u32x4*)(out_rows + row * hd + chunk * 8) = val;
+        if (row < n_rows) __builtin_nontemporal_store(val, (u32x4*)(out_rows + row * hd + chunk * 8));
     }
 }
 

@@ -223,7 +223,7 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
         for (int i = 0; i < O_STORES; ++i) {
             const int row = i * (64 / CHUNKS) + rsub;
             const u32x4 val = *(const u32x4*)(ostage + row * SM::O_STRIDE + chunk * 16);
-            if (row < nq) *(u32x4*)(obase + row * hd + chunk * 8) = val;
+            if (row < nq) __builtin_nontemporal_store(val, (u32x4*)(obase + row * hd + chunk * 8));  // written once, not read back
         }
     }
 }
