@@ -394,6 +394,11 @@ static hipError_t launch_bwd(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_mfma_bwd(const AttnParams& p, void*, hipStream_t stream) {
     const bool one_block = p.max_q <= 32;
     if (p.d == 128) return one_block ? launch_bwd<128, 1, 4>(p, stream) : launch_mfma_bwd_pair(p, stream);
+    // d = 64: two waves per (example, head) keep the LDS footprint small when there are many items;
+    // with few items (less than about two per SIMD) the longest history sets the time, and four
+    // waves walk it twice as fast
+    const bool few_items = (int64_t)p.B * p.H <= 2048;
+    if (few_items) return one_block ? launch_bwd<64, 1, 4>(p, stream) : launch_bwd<64, 2, 4>(p, stream);
     return one_block ? launch_bwd<64, 1, 2>(p, stream) : launch_bwd<64, 2, 2>(p, stream);
 }
 
