@@ -65,7 +65,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this library runs on ONE GPU (no collectives, no sharding); --gpus must be 1. "
-              "See DESIGN.md for how the path would shard by example.", file=sys.stderr)
+              "The path would shard by example: every example is independent.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
