@@ -1,0 +1,95 @@
+"""GPU parity on seeded random shapes: every entry point against the CPU oracle with batch size,
+head count, head dimension, query counts (dense or jagged), history lengths (zero included),
+score functions and windows drawn per case, so that rarely used template paths and tile-boundary
+combinations are exercised.  Scores are kept in the regime where the bf16 rounding of the
+weights stays inside the tolerance (small scale, short histories)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_10016_amd import workloads as W
+from tests.helpers import TOL, assert_close, assert_lse_close, offsets_dev, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def kb():
+    from paper_2602_10016_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _draw(seed):
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 7))
+    H = int(rng.choice([1, 2, 3, 8]))
+    d = int(rng.choice([64, 128]))
+    max_q = int(rng.choice([1, 7, 32, 33, 64, 65, 130, 300]))
+    max_kv = int(rng.choice([1, 31, 33, 64, 100, 260]))
+    jagged_q = bool(rng.integers(2))
+    lens_q = rng.integers(0, max_q + 1, size=B) if jagged_q else np.full(B, max_q)
+    lens_q[rng.integers(B)] = max_q
+    lens_kv = rng.integers(0, max_kv + 1, size=B)
+    lens_kv[rng.integers(B)] = max_kv
+    acts = [int(a) for a in rng.integers(0, 6, size=H)]
+    q_off, kv_off = W.offsets_from_lengths(lens_q), W.offsets_from_lengths(lens_kv)
+    bf = lambda shape, s: W.round_to_bf16((rng.standard_normal(shape) * s).astype(np.float32))
+    return dict(B=B, H=H, d=d, max_q=max_q, max_kv=max_kv, jagged_q=jagged_q, q_off=q_off, kv_off=kv_off, acts=acts,
+                q=bf((q_off[-1], H, d), 0.5), k=bf((kv_off[-1], H, d), 0.5), v=bf((kv_off[-1], H, d), 0.5),
+                d_o=bf((q_off[-1], H, d), 1.0), scale=0.4 / math.sqrt(d), rng=rng)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_gdpa_forward_backward_random_shapes(kb, oracle, seed):
+    c = _draw(seed)
+    what = f"seed {seed}: B={c['B']} H={c['H']} d={c['d']} max_q={c['max_q']} max_kv={c['max_kv']} jagged_q={c['jagged_q']} acts={c['acts']}"
+    q, k, v, d_o = [to_dev(c[n], "bf16") for n in ("q", "k", "v", "d_o")]
+    qo = offsets_dev(c["q_off"]) if c["jagged_q"] else None
+    kvo = offsets_dev(c["kv_off"])
+    o, lse = kb.gdpa_fwd(q, k, v, kvo, c["scale"], 0, q_offsets=qo, max_q=c["max_q"], max_kv=c["max_kv"], head_act=c["acts"])
+    dq, dk, dv = kb.gdpa_bwd(q, k, v, d_o, kvo, c["scale"], 0, o=o, lse=lse, q_offsets=qo, max_q=c["max_q"],
+                             max_kv=c["max_kv"], head_act=c["acts"])
+    torch.cuda.synchronize()
+    kw = dict(q_offsets=c["q_off"], max_q=None, head_act=c["acts"])
+    o_ref, lse_ref = oracle.gdpa_fwd(c["q"], c["k"], c["v"], c["kv_off"], c["scale"], 0, **kw)
+    assert_close(to_np(o), o_ref, TOL["bf16"], what + " O")
+    for h, a in enumerate(c["acts"]):
+        if a == 0:
+            assert_lse_close(to_np(lse)[h], lse_ref[h], 1e-2, what + f" lse h={h}")
+    dq_ref, dk_ref, dv_ref = oracle.gdpa_bwd(c["q"], c["k"], c["v"], c["d_o"], c["kv_off"], c["scale"], 0, **kw)
+    assert_close(to_np(dq), dq_ref, TOL["bf16"], what + " dQ")
+    assert_close(to_np(dk), dk_ref, TOL["bf16"], what + " dK")
+    assert_close(to_np(dv), dv_ref, TOL["bf16"], what + " dV")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_sliding_window_forward_backward_random_shapes(kb, oracle, seed):
+    rng = np.random.default_rng(2000 + seed)
+    B = int(rng.integers(1, 6))
+    H = int(rng.choice([1, 2, 4]))
+    d = int(rng.choice([64, 128]))
+    max_len = int(rng.choice([1, 30, 129, 260, 400]))
+    lens = rng.integers(0, max_len + 1, size=B)
+    lens[rng.integers(B)] = max_len
+    left = int(rng.choice([-1, 0, 5, 31, 32, 100, 255, 1000]))
+    right = int(rng.choice([-1, 0, 0, 3, 40, 128]))
+    off = W.offsets_from_lengths(lens)
+    bf = lambda s: W.round_to_bf16((rng.standard_normal((off[-1], H, d)) * s).astype(np.float32))
+    qn, kn, vn, don = bf(0.5), bf(0.5), bf(0.5), bf(1.0)
+    scale = 0.5 / math.sqrt(d)
+    what = f"seed {seed}: B={B} H={H} d={d} lens={list(lens)} window=({left},{right})"
+    q, k, v, d_o = [to_dev(a, "bf16") for a in (qn, kn, vn, don)]
+    offd = offsets_dev(off)
+    o, lse = kb.swa_fwd(q, k, v, offd, left, right, scale, max_len=max_len)
+    dq, dk, dv = kb.swa_bwd(q, k, v, o, lse, d_o, offd, left, right, scale, max_len=max_len)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.swa_fwd(qn, kn, vn, off, left, right, scale)
+    assert_close(to_np(o), o_ref, TOL["bf16"], what + " O")
+    assert_lse_close(to_np(lse), lse_ref, 1e-2, what + " lse")
+    dq_ref, dk_ref, dv_ref = oracle.swa_bwd(qn, kn, vn, don, off, left, right, scale)
+    assert_close(to_np(dq), dq_ref, TOL["bf16"], what + " dQ")
+    assert_close(to_np(dk), dk_ref, TOL["bf16"], what + " dK")
+    assert_close(to_np(dv), dv_ref, TOL["bf16"], what + " dV")
