@@ -241,6 +241,24 @@ def main():
         other["pffn_direction_gdpa_bwd"] = entry(*t, 3 * w3.total_kv * elt + 4 * w3.B * n_ctx * elt,
                                                  10.0 * w3.d * w3.H * n_ctx * w3.total_kv)
 
+        # The step's three calls on the same batch at head dimension 32 (a 256-wide layer with 8
+        # heads, the paper's example of a click-sequence layer): a quarter of the bytes.
+        d32 = 32
+        q32 = device_normal(torch, (B * Nq, H, d32), r["sigma"], 51)
+        k32 = device_normal(torch, (T, H, d32), r["sigma"], 52)
+        v32 = device_normal(torch, (T, H, d32), r["sigma"], 53)
+        do32 = device_normal(torch, (B * Nq, H, d32), 1.0, 54)
+        qs32 = device_normal(torch, (T, H, d32), r["sigma"], 55)
+        o32, os32 = torch.empty_like(q32), torch.empty_like(qs32)
+        t = timed(lambda: kb.gdpa_fwd(q32, k32, v32, off, scale_gdpa, act, max_q=Nq, max_kv=max_kv, out=o32, want_lse=False, workspace=ws_f), n=10)
+        h32 = {"gdpa_fwd": entry(*t, W.gdpa_bytes(H, d32, B * Nq, T), W.gdpa_flops(H, d32, Nq, T))}
+        t = timed(lambda: kb.gdpa_bwd(q32, k32, v32, do32, off, scale_gdpa, act, max_q=Nq, max_kv=max_kv, workspace=ws_b), n=10)
+        h32["gdpa_bwd"] = entry(*t, W.gdpa_bytes(H, d32, B * Nq, T, backward=True), W.gdpa_flops(H, d32, Nq, T, backward=True))
+        t = timed(lambda: kb.swa_fwd(qs32, k32, v32, off, WINDOW[0], WINDOW[1], 1.0 / math.sqrt(d32), max_len=max_kv, out=os32, want_lse=False, workspace=ws_s), n=10)
+        h32["swa_fwd"] = entry(*t, W.swa_bytes(H, d32, T), W.swa_flops(H, d32, pairs))
+        other["cfg4_batch_at_head_dim_32"] = h32
+        del q32, k32, v32, do32, qs32, o32, os32
+
         # SumKronLinear (stage 3 of hierarchical seed pooling) at the paper's typical configuration:
         # matrix-core-bound (about 570 flop per byte of X).
         Bk, Sk, Tk, Dk, kk = 1024, 256, 32, 384, 8

@@ -368,7 +368,7 @@ __global__ __launch_bounds__(64 * NW) void gdpa_bwd_mfma_kernel(AttnParams p) {
 }
 
 bool mfma_bwd_supported(const AttnParams& p, int dtype) {
-    return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128) && p.max_q >= 1 && p.max_q <= 64;
+    return dtype == KUNLUN_BF16 && (p.d == 32 || p.d == 64 || p.d == 128) && p.max_q >= 1 && p.max_q <= 64;
 }
 
 size_t mfma_bwd_workspace_tail(int, int, int, int, int64_t) { return 0; }
@@ -394,6 +394,7 @@ static hipError_t launch_bwd(const AttnParams& p, hipStream_t stream) {
 hipError_t launch_mfma_bwd(const AttnParams& p, void*, hipStream_t stream) {
     const bool one_block = p.max_q <= 32;
     if (p.d == 128) return one_block ? launch_bwd<128, 1, 4>(p, stream) : launch_mfma_bwd_pair(p, stream);
+    if (p.d == 32) return one_block ? launch_bwd<32, 1, 4>(p, stream) : launch_bwd<32, 2, 4>(p, stream);
     // d = 64: two waves per (example, head) keep the LDS footprint small when there are many items;
     // with few items (less than about two per SIMD) the longest history sets the time, and four
     // waves walk it twice as fast

@@ -340,7 +340,7 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
         const uint32_t dst = lds0 + stage * SM::STAGE;
         dma.issue(Q + qt * tile_bytes, nq_all - qt * KT, dst);
         dma.issue(DO + qt * tile_bytes, nq_all - qt * KT, dst + SM::TILE);
-        if (SOFTMAX) {  // every wave sends the same two loads (equal load counts in all waves); indices clamped
+        if (SOFTMAX && dma.active()) {  // every loading wave sends the same two loads (equal load counts); indices clamped
             const int qi = qt * KT + lane;
             const uint32_t voff = (uint32_t)(qi < nq_all ? qi : nq_all - 1) * 4;
             load_to_lds_b32(lse_rsrc, voff, 0, dst + 2 * SM::TILE);
@@ -498,7 +498,7 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
 
 // work mapping of tile_map.h in both passes
 template <int D, int NW, bool WINDOWED>
-__global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dq_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(64 * NW, D == 128 ? 2 : 3) void bwd_dq_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                             const int32_t* __restrict__ tile_example, int runs,
                                                             const float* __restrict__ delta_ws) {
     __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, 0>::TOTAL];
@@ -519,7 +519,7 @@ __global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dq_kernel(AttnPa
 }
 
 template <int D, int NW, bool WINDOWED>
-__global__ __launch_bounds__(64 * NW, D == 64 ? 3 : 2) void bwd_dkdv_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(64 * NW, D == 128 ? 2 : 3) void bwd_dkdv_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                               const int32_t* __restrict__ tile_example, int runs,
                                                               const float* __restrict__ delta_ws) {
     __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, STATS_BYTES>::TOTAL + (D == 128 ? 3 : 0) * NW * 1024];
@@ -563,7 +563,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t* __restrict__ o
 }
 
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype) {
-    return dtype == KUNLUN_BF16 && (p.d == 64 || p.d == 128);
+    return dtype == KUNLUN_BF16 && (p.d == 32 || p.d == 64 || p.d == 128);
 }
 
 size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv) {
@@ -599,8 +599,11 @@ static hipError_t launch_tiled(const AttnParams& p, char* ws, bool any_softmax, 
 
 hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool any_softmax, hipStream_t stream) {
     char* ws = (char*)workspace_tail;
-    if (p.windowed) return p.d == 128 ? launch_tiled<128, true>(p, ws, true, stream) : launch_tiled<64, true>(p, ws, true, stream);
-    return p.d == 128 ? launch_tiled<128, false>(p, ws, any_softmax, stream) : launch_tiled<64, false>(p, ws, any_softmax, stream);
+    if (p.windowed)
+        return p.d == 128 ? launch_tiled<128, true>(p, ws, true, stream)
+               : p.d == 64 ? launch_tiled<64, true>(p, ws, true, stream) : launch_tiled<32, true>(p, ws, true, stream);
+    return p.d == 128 ? launch_tiled<128, false>(p, ws, any_softmax, stream)
+           : p.d == 64 ? launch_tiled<64, false>(p, ws, any_softmax, stream) : launch_tiled<32, false>(p, ws, any_softmax, stream);
 }
 
 }  // namespace kunlun

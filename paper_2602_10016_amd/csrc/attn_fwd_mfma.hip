@@ -32,7 +32,7 @@ namespace kunlun {
 template <int D>
 struct FwdSmem {
     static constexpr int K_STRIDE = D * 2 + 16;
-    static constexpr int V_STRIDE = D * 2 + 64;
+    static constexpr int V_STRIDE = D == 32 ? 64 : D * 2 + 64;  // (D = 32: four rows of 64 bytes already cover all banks)
     static constexpr int K_TILE = KT * K_STRIDE;
     static constexpr int V_TILE = KT * V_STRIDE;
     static constexpr int BUF_BYTES = K_TILE + V_TILE;  // K tile, then V tile
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
 }
 
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
-    if (dtype != KUNLUN_BF16 || (p.d != 64 && p.d != 128)) return false;
+    if (dtype != KUNLUN_BF16 || (p.d != 32 && p.d != 64 && p.d != 128)) return false;
     // the online softmax takes the row maximum before scaling: it needs scale > 0
     // (other scales are served by the generic kernels)
     for (int h = 0; h < p.H; ++h)
@@ -340,8 +340,11 @@ hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
     // 32 queries per wave, up to 255 registers per wave, two or three waves per SIMD.
     // Query-tiled launches use 128-query tiles (4 waves): fewer K/V tile loads per query.
     if (mfma_fwd_is_qtiled(p)) return launch_mfma_fwd_qtiled(p, stream);
-    if (p.max_q <= 32) return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream) : launch_gdpa<64, 1, 1, 2>(p, stream);
-    return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream) : launch_gdpa<64, 1, 2, 2>(p, stream);
+    if (p.max_q <= 32)
+        return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream)
+               : p.d == 64 ? launch_gdpa<64, 1, 1, 2>(p, stream) : launch_gdpa<32, 1, 1, 2>(p, stream);
+    return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream)
+           : p.d == 64 ? launch_gdpa<64, 1, 2, 2>(p, stream) : launch_gdpa<32, 1, 2, 2>(p, stream);
 }
 
 }  // namespace kunlun

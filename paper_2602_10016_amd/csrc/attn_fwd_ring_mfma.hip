@@ -272,8 +272,11 @@ static hipError_t launch_qtiled(const AttnParams& p, hipStream_t stream) {
 // p.order points at tile_table_bytes(B, total_q) bytes of workspace.
 hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, hipStream_t stream) {
     // 128-query tiles (4 waves of 32 queries)
-    if (p.windowed) return p.d == 128 ? launch_qtiled<128, 4, 2, true>(p, stream) : launch_qtiled<64, 4, 2, true>(p, stream);
-    return p.d == 128 ? launch_qtiled<128, 4, 2, false>(p, stream) : launch_qtiled<64, 4, 2, false>(p, stream);
+    if (p.windowed)
+        return p.d == 128 ? launch_qtiled<128, 4, 2, true>(p, stream)
+               : p.d == 64 ? launch_qtiled<64, 4, 2, true>(p, stream) : launch_qtiled<32, 4, 2, true>(p, stream);
+    return p.d == 128 ? launch_qtiled<128, 4, 2, false>(p, stream)
+           : p.d == 64 ? launch_qtiled<64, 4, 2, false>(p, stream) : launch_qtiled<32, 4, 2, false>(p, stream);
 }
 
 }  // namespace kunlun

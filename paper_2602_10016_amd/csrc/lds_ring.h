@@ -55,23 +55,28 @@ enum { SWZ_K = 0, SWZ_V = 1, SWZ_U = 2 };
 // The chunk XOR of a tile row for each swizzle kind (see TileLayout).
 template <int D, int SWZ>
 __device__ __forceinline__ int swizzle_of_row(int row) {
-    if (SWZ == SWZ_K) return (D == 128) ? (row & 15) : ((row >> 1) & 7);
-    if (SWZ == SWZ_V) return ((D == 128) ? (row & 3) : ((row >> 1) & 1)) << 2;
+    if (SWZ == SWZ_K) return (D == 128) ? (row & 15) : (D == 64) ? ((row >> 1) & 7) : ((row >> 2) & 3);
+    if (SWZ == SWZ_V) return ((D == 128) ? (row & 3) : (D == 64) ? ((row >> 1) & 1) : 0) << 2;
     return TileLayout<D>::u_swizzle(row);
 }
 
 // A wave's share of the loads of one 32-row tile, cooperatively with the NW waves of the
 // workgroup: load instruction j = wave*IPW + i fills the LDS bytes [1024 j, 1024 (j+1)) of the
-// tile, i.e. rows RPI*j ..  Every load stays inside the valid rows of the tile: rows past the
-// end fetch the last valid row again (finite data; the kernels give them zero weight).
+// tile, i.e. rows RPI*j ..  A tile of fewer than NW instructions (D = 32 with four waves) is
+// loaded by the first ACTIVE_WAVES waves alone; the others issue nothing.  Every load stays
+// inside the valid rows of the tile: rows past the end fetch the last valid row again (finite
+// data; the kernels give them zero weight).
 template <int D, int NW, int SWZ>
 struct TileDma {
     static constexpr int ROW = D * 2;
     static constexpr int TILE = KT * ROW;
     static constexpr int CHUNKS = D / 8;
     static constexpr int RPI = 1024 / ROW;        // rows written by one load instruction
-    static constexpr int IPW = TILE / 1024 / NW;  // load instructions per wave per tile
-    static_assert(IPW >= 1 && TILE % (1024 * NW) == 0, "tile does not split evenly over the waves");
+    static constexpr int INSTR = TILE / 1024;     // load instructions per tile
+    static constexpr int IPW = INSTR >= NW ? INSTR / NW : 1;  // load instructions per (active) wave per tile
+    static constexpr int ACTIVE_WAVES = INSTR / IPW;
+    static_assert(ACTIVE_WAVES >= 1 && ACTIVE_WAVES <= NW && ACTIVE_WAVES * IPW * 1024 == TILE,
+                  "tile does not split evenly over the waves");
     uint32_t voff[IPW], row_bytes;
     int lane_, wave_;
 
@@ -90,8 +95,10 @@ struct TileDma {
         }
     }
     // tile_base: first row of the tile (this head's columns); rows_left: valid rows from there
-    // on (>= 1); lds_tile: LDS address of the tile.  Issues IPW loads.
+    // on (>= 1); lds_tile: LDS address of the tile.  Issues IPW loads (none in an idle wave).
+    __device__ __forceinline__ bool active() const { return ACTIVE_WAVES == NW || wave_ < ACTIVE_WAVES; }
     __device__ __forceinline__ void issue(const char* tile_base, int rows_left, uint32_t lds_tile) const {
+        if (!active()) return;
         const int rows = rows_left < KT ? rows_left : KT;
         const u32x4 rsrc = make_rsrc_words(tile_base, (uint32_t)(rows - 1) * row_bytes + ROW);
         const uint32_t dst = lds_tile + wave_ * IPW * 1024;

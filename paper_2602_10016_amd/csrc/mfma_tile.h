@@ -37,6 +37,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // no padding) with XOR swizzles that keep both access patterns free of bank conflicts.
 template <int D>
 struct TileLayout {
+    static_assert(D == 32 || D == 64 || D == 128, "head dimensions of the matrix-core kernels");
     static constexpr int ROW_BYTES = D * 2;
     static constexpr int TILE_BYTES = KT * ROW_BYTES;
     static constexpr int CHUNKS = D / 8;        // 16-byte chunks per row
@@ -46,20 +47,21 @@ struct TileLayout {
     // K tiles: read as A operand (lane: row r, chunk 2*kc+g).  16 consecutive rows must hit
     // 16 different chunk positions.
     __device__ static __forceinline__ int k_offset(int row, int chunk) {
-        const int x = (D == 128) ? (row & 15) : ((row >> 1) & 7);
+        const int x = (D == 128) ? (row & 15) : (D == 64) ? ((row >> 1) & 7) : ((row >> 2) & 3);
         return row * ROW_BYTES + ((chunk ^ x) << 4);
     }
     // V tiles: read with the transposing LDS read, 4 consecutive rows x 64 bytes per 32 lanes.
-    // The four rows must sit in four different 64-byte bank groups.
+    // The four rows must sit in four different 64-byte bank groups (D = 32: a row IS 64 bytes).
     __device__ static __forceinline__ int v_offset(int row, int byte_in_row) {
-        const int x = (D == 128) ? (row & 3) : ((row >> 1) & 1);
+        const int x = (D == 128) ? (row & 3) : (D == 64) ? ((row >> 1) & 1) : 0;
         return row * ROW_BYTES + ((((byte_in_row >> 6) ^ x)) << 6) + (byte_in_row & 63);
     }
     // Tiles that are read BOTH ways (backward pass: K, Q, dO): one swizzle that satisfies both
     // conditions above.  D = 128: chunk ^= 4*(row%4) + (row/4)%4;  D = 64: chunk ^= bit-reversed
-    // (row/2)%8.
+    // (row/2)%8;  D = 32: chunk ^= (row/4)%4.
     __device__ static __forceinline__ int u_swizzle(int row) {
         if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+        if (D == 32) return (row >> 2) & 3;
         const int x = (row >> 1) & 7;
         return ((x & 1) << 2) | (x & 2) | ((x >> 2) & 1);
     }

@@ -82,7 +82,8 @@ def test_cfg2_forward_all_activations_nonlinear_range(kb, oracle, act, strength,
 RAGGED = [0, 1, 31, 32, 33, 63, 64, 65, 95, 97, 128, 1, 0, 200, 511, 3]
 
 
-@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 8), (64, 40), (64, 64), (128, 64), (128, 33), (128, 100), (128, 1), (64, 130)])
+@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 8), (64, 40), (64, 64), (128, 64), (128, 33), (128, 100), (128, 1), (64, 130), (32, 8), (32, 64),
+                                  (32, 33), (32, 130)])
 @pytest.mark.parametrize("act", ["gelu", "softmax"])
 def test_ragged_tails_and_query_counts(kb, oracle, d, Nq, act):
     wl = W.make("cfg2", 3, B=len(RAGGED), H=3, d=d, Nq=Nq, lengths=("list", RAGGED), scale=0.5 / math.sqrt(d))
@@ -108,7 +109,7 @@ def test_jagged_queries(kb, oracle):
         check_gdpa_fwd(kb, oracle, wl, act)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_long_jagged_queries_few_keys(kb, oracle, d):
     """The PFFN direction of Eq. (GDPA): the sequence tokens are the queries, a few context
     tokens per example are keys and values (query-tiled launch)."""
@@ -187,7 +188,7 @@ def test_cfg3_sliding_window(kb, oracle):
 
 
 @pytest.mark.parametrize("window", [(255, 0), (0, 0), (3, 3), (50, 50), (100, 7), (31, 0), (32, 0), (64, 64), (-1, 0), (-1, -1), (0, -1), (1000, 1000)])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_swa_windows_and_ragged_lengths(kb, oracle, window, d):
     lens = [1, 0, 63, 64, 65, 127, 129, 300, 2, 777, 33]
     wl = W.make("cfg3", 1, B=len(lens), H=2, d=d, lengths=("list", lens))
@@ -223,7 +224,7 @@ def check_swa_bwd(kb, oracle, wl, window):
 
 
 @pytest.mark.parametrize("window", [(255, 0), (3, 3), (0, 0), (40, 7), (-1, 0), (-1, -1), (127, 128), (0, 200)])
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 32)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("bf16", 32), ("fp32", 32)])
 def test_swa_backward(kb, oracle, window, dtype, d):
     lens = [1, 0, 63, 64, 65, 130, 300, 2, 33, 513]
     sigma = 0.5 if dtype == "bf16" else 1.0
@@ -385,14 +386,14 @@ def test_backward_all_activations_nonlinear_range(kb, oracle, act, strength, len
     check_gdpa_bwd(kb, oracle, wl, ACTS[act])
 
 
-@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 20), (128, 64), (128, 40), (64, 70)])
+@pytest.mark.parametrize("d,Nq", [(64, 32), (64, 20), (128, 64), (128, 40), (64, 70), (32, 32), (32, 20), (32, 64), (32, 70)])
 def test_backward_ragged(kb, oracle, d, Nq):
     wl = W.make("cfg5", 2, B=len(RAGGED), H=2, d=d, Nq=Nq, lengths=("list", RAGGED), scale=0.5 / math.sqrt(d))
     for act in (3, 0):
         check_gdpa_bwd(kb, oracle, wl, act)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 @pytest.mark.parametrize("act", list(ACTS))
 def test_backward_long_jagged_queries_few_keys(kb, oracle, d, act):
     """Backward in the PFFN direction (sequence tokens are the queries): two-pass matrix-core path."""

@@ -26,7 +26,7 @@ def _draw(seed):
     rng = np.random.default_rng(1000 + seed)
     B = int(rng.integers(1, 7))
     H = int(rng.choice([1, 2, 3, 8]))
-    d = int(rng.choice([64, 128]))
+    d = int(rng.choice([32, 64, 128]))
     max_q = int(rng.choice([1, 7, 32, 33, 64, 65, 130, 300]))
     max_kv = int(rng.choice([1, 31, 33, 64, 100, 260]))
     jagged_q = bool(rng.integers(2))
@@ -70,7 +70,7 @@ def test_sliding_window_forward_backward_random_shapes(kb, oracle, seed):
     rng = np.random.default_rng(2000 + seed)
     B = int(rng.integers(1, 6))
     H = int(rng.choice([1, 2, 4]))
-    d = int(rng.choice([64, 128]))
+    d = int(rng.choice([32, 64, 128]))
     max_len = int(rng.choice([1, 30, 129, 260, 400]))
     lens = rng.integers(0, max_len + 1, size=B)
     lens[rng.integers(B)] = max_len
