@@ -44,7 +44,7 @@
  * one stream.  Offsets are trusted: offsets[0] = 0, non-decreasing, offsets[B] = total.
  *
  * Data types.  KUNLUN_BF16: bf16 storage, fp32 accumulation, outputs rounded to nearest
- * even; the two contractions run on the matrix cores when d is 64 or 128.  KUNLUN_FP32:
+ * even; the two contractions run on the matrix cores when d is 32, 64 or 128.  KUNLUN_FP32:
  * fp32 storage and arithmetic throughout.  Supported d: multiples of 8 up to 256.
  *
  * Errors.  Every entry point validates its arguments on the host before anything is
