@@ -271,7 +271,13 @@ def main():
         fl = 2.0 * Bk * kk * Tk * Dk * (Sk + Dk)
         other["sumkron_fwd_S256_T32_D384_k8_B1024"] = {"us": round(tc, 1), "us_warm": round(tw, 1), "tflops": round(fl / tc / 1e6, 1),
                                                        "pct_mfma_peak": round(100 * fl / (tc * 1e-6) / MFMA_BF16_PEAK, 2)}
-        del xk, yk, wsk
+        dyk = device_normal(torch, (Bk, Tk, Dk), 1.0, 44)
+        wsb = torch.empty(kb.sumkron_bwd_workspace_bytes(Bk, Sk, Tk, Dk, kk), dtype=torch.uint8, device="cuda")
+        tw, tc = timed(lambda: kb.sumkron_bwd(xk, zk, wk, dyk, workspace=wsb), n=10)
+        fl = 2.0 * Bk * kk * Tk * Dk * (3 * Sk + 2 * Dk)   # U, G, dX, dW, dZ: each intermediate computed once
+        other["sumkron_bwd_S256_T32_D384_k8_B1024"] = {"us": round(tc, 1), "us_warm": round(tw, 1), "tflops": round(fl / tc / 1e6, 1),
+                                                       "pct_mfma_peak": round(100 * fl / (tc * 1e-6) / MFMA_BF16_PEAK, 2)}
+        del xk, yk, wsk, dyk, wsb
 
         # Diagnostic, not a workload of the paper: the same forward entry point on a shape that IS
         # matrix-core-bound (512 queries per example: 512 flop per K/V byte, above the ridge), to show

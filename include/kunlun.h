@@ -23,6 +23,7 @@
  *   kunlun_sumkron_fwd  SumKronLinear, Eq. (SumKronLinear) of Sec. "Hierarchical Seed Pooling"
  *                    (stage 3: compression of the S pooled seeds to T tokens):
  *                        Y_b = sum_{i=1..k} Z_i^T X_b W_i .
+ *   kunlun_sumkron_bwd  Gradient of <Y, dY> of the same with respect to X, Z_i and W_i.
  *
  * Jagged layout.  A batch holds B examples.  Tensors are packed "tokens, heads, channels":
  *   Q  [total_q,  H, d]      O, dO, dQ like Q
@@ -170,6 +171,25 @@ int kunlun_sumkron_fwd(const void* x, const void* z, const void* w, void* y, int
 
 /* Bytes of workspace that kunlun_sumkron_fwd needs for these sizes (0 for invalid sizes). */
 size_t kunlun_sumkron_workspace_bytes(int B, int S, int T, int D, int k, int dtype);
+
+/*
+ * SumKronLinear backward: the gradients of <Y, dY> for Y of Eq. (SumKronLinear),
+ *     dX[b] = sum_i Z[i] dY[b] W[i]^T,   dZ[i] = sum_b X[b] W[i] dY[b]^T,   dW[i] = sum_b X[b]^T Z[i] dY[b].
+ *   x, z, w  in, device, as in kunlun_sumkron_fwd
+ *   dy  in,  device, [B, T, D]   gradient with respect to Y
+ *   dx  out, device, [B, S, D];  dz out, device, [k, S, T];  dw out, device, [k, D, D]   fully overwritten
+ * KUNLUN_BF16: five matrix-core contractions with fp32 accumulation when, in addition to the forward
+ * conditions, S is a multiple of 128 and T*k and B*T are multiples of 32; Z_i^T X_b and dY_b W_i^T are
+ * recomputed and rounded to bf16 once, the two sums over the batch are accumulated in fp32 partial
+ * sums that are added in a fixed order (results are bit-reproducible).  Other shapes and KUNLUN_FP32
+ * take plain fp32 kernels.  workspace: device, at least kunlun_sumkron_bwd_workspace_bytes(...) bytes,
+ * 256-byte aligned.  B == 0 is legal: dz and dw are set to zero.  Errors as for the other entry points.
+ */
+int kunlun_sumkron_bwd(const void* x, const void* z, const void* w, const void* dy, void* dx, void* dz, void* dw, int B, int S,
+                       int T, int D, int k, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace that kunlun_sumkron_bwd needs for these sizes (0 for invalid sizes). */
+size_t kunlun_sumkron_bwd_workspace_bytes(int B, int S, int T, int D, int k, int dtype);
 
 /* Static, human-readable text for a kunlun_status. */
 const char* kunlun_strerror(int status);

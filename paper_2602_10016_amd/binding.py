@@ -22,7 +22,8 @@ BF16, FP32 = 0, 1
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
-           "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_strerror"]
+           "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
+           "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -42,6 +43,10 @@ _lib.kunlun_sumkron_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, 
 _lib.kunlun_sumkron_fwd.restype = _i
 _lib.kunlun_sumkron_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
 _lib.kunlun_sumkron_workspace_bytes.restype = _sz
+_lib.kunlun_sumkron_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]
+_lib.kunlun_sumkron_bwd.restype = _i
+_lib.kunlun_sumkron_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
+_lib.kunlun_sumkron_bwd_workspace_bytes.restype = _sz
 _lib.kunlun_strerror.argtypes = [_i]
 _lib.kunlun_strerror.restype = ctypes.c_char_p
 
@@ -185,3 +190,20 @@ def sumkron_fwd(x, z, w, *, out=None, workspace=None, stream=None):
     if rc != OK:
         raise KunlunError(rc)
     return y
+
+
+def sumkron_bwd_workspace_bytes(B, S, T, D, k, dtype=BF16) -> int:
+    return int(_lib.kunlun_sumkron_bwd_workspace_bytes(B, S, T, D, k, dtype))
+
+
+def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
+    """kunlun_sumkron_bwd.  x [B,S,D], z [k,S,T], w [k,D,D], dy [B,T,D] device tensors; returns (dx, dz, dw)."""
+    B, S, D = x.shape
+    k, _, T = z.shape
+    dx, dz, dw = torch.empty_like(x), torch.empty_like(z), torch.empty_like(w)
+    ws = _workspace(workspace, sumkron_bwd_workspace_bytes(B, S, T, D, k, _dtype_code(x)), x.device)
+    rc = _lib.kunlun_sumkron_bwd(_ptr(x), _ptr(z), _ptr(w), _ptr(dy), _ptr(dx), _ptr(dz), _ptr(dw), B, S, T, D, k,
+                                 _dtype_code(x), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return dx, dz, dw

@@ -68,12 +68,38 @@ int kunlun_sumkron_fwd(const void* x, const void* z, const void* w, void* y, int
     if (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32) return KUNLUN_ERR_UNSUPPORTED;
     // 32-bit index arithmetic inside a row block of the kernels
     if ((int64_t)k * D > (1 << 20) || (int64_t)k * T > (1 << 20) || S > (1 << 20) || D % 8 != 0) return KUNLUN_ERR_UNSUPPORTED;
+    if ((int64_t)B * T >= (1ll << 31) || (int64_t)B * S >= (1ll << 31)) return KUNLUN_ERR_UNSUPPORTED;
     if (B == 0) return KUNLUN_OK;
     if (!x || !z || !w || !y) return KUNLUN_ERR_NULL;
     if (!aligned(x, 16) || !aligned(z, 16) || !aligned(w, 16) || !aligned(y, 16)) return KUNLUN_ERR_ALIGN;
     if (!workspace || workspace_bytes < kunlun_sumkron_workspace_bytes(B, S, T, D, k, dtype)) return KUNLUN_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
     const hipError_t e = launch_sumkron(x, z, w, y, B, S, T, D, k, dtype, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
+size_t kunlun_sumkron_bwd_workspace_bytes(int B, int S, int T, int D, int k, int dtype) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0 || (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32)) return 0;
+    return sumkron_bwd_workspace(B, S, T, D, k, dtype) + 256;
+}
+
+int kunlun_sumkron_bwd(const void* x, const void* z, const void* w, const void* dy, void* dx, void* dz, void* dw, int B, int S,
+                       int T, int D, int k, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 0 || S <= 0 || T <= 0 || D <= 0 || k <= 0) return KUNLUN_ERR_SHAPE;
+    if (dtype != KUNLUN_BF16 && dtype != KUNLUN_FP32) return KUNLUN_ERR_UNSUPPORTED;
+    // 32-bit index arithmetic inside a row block of the kernels, and 32-bit row / contraction counts
+    if ((int64_t)k * D > (1 << 20) || (int64_t)k * T > (1 << 20) || S > (1 << 20) || D % 8 != 0) return KUNLUN_ERR_UNSUPPORTED;
+    if ((int64_t)B * T >= (1ll << 31) || (int64_t)B * D >= (1ll << 31) || (int64_t)B * S >= (1ll << 31)) return KUNLUN_ERR_UNSUPPORTED;
+    if (!z || !w || !dz || !dw) return KUNLUN_ERR_NULL;
+    if (B > 0 && (!x || !dy || !dx)) return KUNLUN_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(z, 16) || !aligned(w, 16) || !aligned(dy, 16) || !aligned(dx, 16) || !aligned(dz, 16) ||
+        !aligned(dw, 16))
+        return KUNLUN_ERR_ALIGN;
+    if (B > 0) {
+        if (!workspace || workspace_bytes < kunlun_sumkron_bwd_workspace_bytes(B, S, T, D, k, dtype)) return KUNLUN_ERR_WORKSPACE;
+        if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+    }
+    const hipError_t e = launch_sumkron_bwd(x, z, w, dy, dx, dz, dw, B, S, T, D, k, dtype, workspace, (hipStream_t)stream);
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 

@@ -63,6 +63,10 @@ hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool
 size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype);
 hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
                           int dtype, void* workspace, hipStream_t stream);
+bool sumkron_bwd_tiled_supported(int B, int S, int T, int D, int k, int dtype);
+size_t sumkron_bwd_workspace(int B, int S, int T, int D, int k, int dtype);
+hipError_t launch_sumkron_bwd(const void* x, const void* z, const void* w, const void* dy, void* dx, void* dz, void* dw, int B,
+                              int S, int T, int D, int k, int dtype, void* workspace, hipStream_t stream);
 
 #ifdef __HIPCC__
 // ---- device helpers ----

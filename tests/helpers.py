@@ -36,6 +36,23 @@ def assert_close(got, ref, tol, what=""):
         assert err.max() / scale <= tol, f"{what}: max err {err.max():.3e} vs max |ref| {scale:.3e} (tol {tol})"
 
 
+def assert_close_sums(got, ref, tol, what=""):
+    """Criterion for outputs that are sums of many products whose factors were rounded to bf16 on
+    the way (weight gradients: sums over the batch).  The rounding errors of the terms add up like
+    a random walk: their total is about 2^-9 / sqrt(3) times the root of the sum of the squared
+    terms, which is the typical magnitude (RMS) of the outputs themselves, whatever the value of
+    the one output at hand.  So: |x - r| <= tol (rms(ref) + |r|) for every element.  A misplaced
+    or missing operand changes outputs by the order of rms(ref) and fails."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values in the GPU result"
+    err = np.abs(got - ref)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    bad = err > tol * (rms + np.abs(ref))
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond tol, worst {err.max():.3e} (rms of ref {rms:.3e})"
+
+
 def assert_lse_close(got, ref, tol, what="lse"):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)

@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 8
+    assert len(declared) == 10
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
@@ -124,3 +124,24 @@ def test_sumkron_argument_validation_without_gpu(kb):
     assert call(ws=0x1010) == kb.ERR_ALIGN
     need = kb.sumkron_workspace_bytes(1024, 256, 32, 384, 8)
     assert need >= 1024 * 32 * 8 * 384 * 2 and kb.sumkron_workspace_bytes(4, 0, 1, 8, 1) == 0
+
+
+def test_sumkron_bwd_argument_validation_without_gpu(kb):
+    lib = kb.raw()
+    call = lambda x=0x1000, z=0x1000, w=0x1000, dy=0x1000, dx=0x1000, dz=0x1000, dw=0x1000, B=2, S=32, T=4, D=128, k=2, \
+        dtype=kb.BF16, ws=0x1000, n=1 << 30: lib.kunlun_sumkron_bwd(x, z, w, dy, dx, dz, dw, B, S, T, D, k, dtype, ws, n, None)
+    assert call(S=0) == kb.ERR_SHAPE and call(k=0) == kb.ERR_SHAPE and call(B=-1) == kb.ERR_SHAPE
+    assert call(dtype=7) == kb.ERR_UNSUPPORTED
+    assert call(D=12) == kb.ERR_UNSUPPORTED
+    assert call(x=None) == kb.ERR_NULL and call(dy=None) == kb.ERR_NULL and call(dx=None) == kb.ERR_NULL
+    assert call(dz=None) == kb.ERR_NULL and call(dw=None) == kb.ERR_NULL and call(w=None) == kb.ERR_NULL
+    assert call(dz=None, B=0) == kb.ERR_NULL      # an empty batch still writes zero weight gradients
+    assert call(dw=0x1004) == kb.ERR_ALIGN
+    assert call(ws=None) == kb.ERR_WORKSPACE and call(n=16) == kb.ERR_WORKSPACE
+    assert call(ws=0x1010) == kb.ERR_ALIGN
+    # tiled path: Zt, Zc, U, G in bf16 and the larger of the two partial-sum buffers
+    need = kb.sumkron_bwd_workspace_bytes(1024, 256, 32, 384, 8)
+    assert need >= 2 * 1024 * 32 * 8 * 384 * 2 and kb.sumkron_bwd_workspace_bytes(4, 0, 1, 8, 1) == 0
+    # plain path: U and G in fp32
+    assert kb.sumkron_bwd_workspace_bytes(3, 40, 6, 24, 3, kb.FP32) >= 2 * 3 * 6 * 3 * 24 * 4
+    assert kb.sumkron_bwd_workspace_bytes(0, 256, 32, 384, 8) > 0     # an empty batch is a legal size

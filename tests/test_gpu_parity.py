@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2602_10016_amd import workloads as W
-from tests.helpers import TOL, assert_close, assert_lse_close, offsets_dev, to_dev, to_np
+from tests.helpers import TOL, assert_close, assert_close_sums, assert_lse_close, offsets_dev, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -481,6 +481,63 @@ def test_sumkron_examples_are_isolated_and_repeatable(kb):
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)
     assert torch.equal(y1[2:5], y3)
+
+
+def _sumkron_dy(seed, B, T, D, dtype):
+    dy = np.random.default_rng(seed).standard_normal((B, T, D), dtype=np.float32)
+    return W.round_to_bf16(dy) if dtype == "bf16" else dy
+
+
+def _check_sumkron_bwd(kb, oracle, B, S, T, D, k, dtype, tol, seed):
+    x, z, w = _sumkron_inputs(seed, B, S, T, D, k, dtype)
+    dy = _sumkron_dy(seed + 1, B, T, D, dtype)
+    dx, dz, dw = kb.sumkron_bwd(to_dev(x, dtype), to_dev(z, dtype), to_dev(w, dtype), to_dev(dy, dtype))
+    torch.cuda.synchronize()
+    rx, rz, rw = oracle.sumkron_bwd(x, z, w, dy)
+    tag = f"sumkron bwd {dtype} B={B} S={S} T={T} D={D} k={k}"
+    assert_close(to_np(dx), rx, tol, tag + " dX")
+    # sums over the batch of products with a bf16-rounded factor: error relative to the typical output
+    check_sums = assert_close_sums if dtype == "bf16" else assert_close
+    check_sums(to_np(dz), rz, tol, tag + " dZ")
+    check_sums(to_np(dw), rw, tol, tag + " dW")
+
+
+@pytest.mark.parametrize("B,S,T,D,k", [(5, 256, 32, 384, 8),     # the paper's typical configuration
+                                       (3, 128, 32, 128, 2),     # one tile in most directions
+                                       (4, 128, 16, 256, 2),     # k*T = 32: a ragged row tile in the dZ contraction
+                                       (2, 256, 48, 128, 2),     # T*k = 96, k*T = 96
+                                       (3, 128, 32, 128, 3),     # k*D = 384: 128-row tiles in the dW contraction
+                                       (2, 128, 16, 128, 6),
+                                       (16, 128, 32, 128, 2)])   # enough rows for several split-K ranges
+def test_sumkron_backward_tiled(kb, oracle, B, S, T, D, k):
+    """bf16 matrix-core path (five tiled GEMMs, two of them split-K).  The intermediates Z^T X and
+    dY W^T (O(1) values) are rounded to bf16 once; sums over the batch are accumulated in fp32."""
+    _check_sumkron_bwd(kb, oracle, B, S, T, D, k, "bf16", TOL["bf16"], 70 + B)
+
+
+@pytest.mark.parametrize("dtype,B,S,T,D,k", [("fp32", 3, 40, 6, 24, 3), ("bf16", 2, 24, 5, 40, 2), ("fp32", 2, 128, 32, 128, 2),
+                                             ("bf16", 2, 64, 32, 128, 2)])   # the last: tiled forward shape, plain backward
+def test_sumkron_backward_plain_kernels(kb, oracle, dtype, B, S, T, D, k):
+    _check_sumkron_bwd(kb, oracle, B, S, T, D, k, dtype, TOL[dtype] if dtype == "bf16" else 2e-5, 80)
+
+
+def test_sumkron_backward_repeatable_and_empty_batch(kb):
+    x, z, w = _sumkron_inputs(81, 16, 128, 32, 128, 2, "bf16")
+    dy = _sumkron_dy(82, 16, 32, 128, "bf16")
+    xd, zd, wd, dyd = to_dev(x, "bf16"), to_dev(z, "bf16"), to_dev(w, "bf16"), to_dev(dy, "bf16")
+    a = kb.sumkron_bwd(xd, zd, wd, dyd)
+    b = kb.sumkron_bwd(xd, zd, wd, dyd)
+    torch.cuda.synchronize()
+    for u, v in zip(a, b):
+        assert torch.equal(u, v)   # partial sums are added in a fixed order
+    # dX of an example depends on that example alone
+    c = kb.sumkron_bwd(xd[4:8].contiguous(), zd, wd, dyd[4:8].contiguous())
+    torch.cuda.synchronize()
+    assert torch.equal(a[0][4:8], c[0])
+    # no example: zero weight gradients
+    e = kb.sumkron_bwd(xd[:0].contiguous(), zd, wd, dyd[:0].contiguous())
+    torch.cuda.synchronize()
+    assert e[0].numel() == 0 and float(e[1].float().abs().max()) == 0.0 and float(e[2].float().abs().max()) == 0.0
 
 
 # ---------------- HIP graph capture ----------------
