@@ -366,7 +366,9 @@ static void plan_splits(int64_t tiles, int n_steps, int target, int& splits, int
     steps_per_split = (int)((n_steps + want - 1) / want);
     splits = (n_steps + steps_per_split - 1) / steps_per_split;
 }
-constexpr int SPLIT_TARGET = 1024;
+// workgroups aimed at: the dW contraction is matrix-core-bound (two workgroups per compute unit, two rounds),
+// the dZ contraction streams X and G once and writes 128 KB of partial sums per workgroup (one round)
+constexpr int SPLIT_TARGET_DW = 1024, SPLIT_TARGET_DZ = 512;
 
 static bool gemm_is_tall(int M, bool a_cols) { return a_cols ? M % 256 == 0 : (M % 256 == 0 || M >= 1024); }
 static int64_t gemm_tiles(int M, int N, int batches, bool a_cols) {
@@ -534,8 +536,8 @@ static BwdLayout sumkron_bwd_layout(int B, int S, int T, int D, int k, int dtype
     l.u = l.zc + align_up((size_t)k * T * S * 2, 256);
     l.gq = l.u + align_up(ukd * 2, 256);
     l.partial = l.gq + align_up(ukd * 2, 256);
-    plan_splits(gemm_tiles(k * D, D, 1, true), (int)((int64_t)B * T / GK), SPLIT_TARGET, l.dw_splits, l.dw_steps);
-    plan_splits(gemm_tiles(k * T, S, 1, false), (int)((int64_t)B * D / GK), SPLIT_TARGET, l.dz_splits, l.dz_steps);
+    plan_splits(gemm_tiles(k * D, D, 1, true), (int)((int64_t)B * T / GK), SPLIT_TARGET_DW, l.dw_splits, l.dw_steps);
+    plan_splits(gemm_tiles(k * T, S, 1, false), (int)((int64_t)B * D / GK), SPLIT_TARGET_DZ, l.dz_splits, l.dz_steps);
     const size_t p1 = (size_t)l.dw_splits * k * D * D * sizeof(float), p2 = (size_t)l.dz_splits * k * T * S * sizeof(float);
     l.total = l.partial + align_up(p1 > p2 ? p1 : p2, 256);
     return l;
