@@ -465,7 +465,8 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(T_* __restrict__ p, int6
     if (idx < n) p[idx] = from_float<T_>(0.f);
 }
 
-// plain kernels: one thread per output element, fp32 throughout; u and gq are [B*T][k][D] fp32
+// plain kernels: one thread per output element, fp32 (the two sums over the batch accumulate in fp64);
+// u and gq are [B*T][k][D] fp32
 template <typename T_>
 __global__ __launch_bounds__(256) void sumkron_g_plain(const T_* __restrict__ dy, const T_* __restrict__ w, float* __restrict__ gq,
                                                        int64_t rows, int D, int k) {
@@ -500,9 +501,9 @@ __global__ __launch_bounds__(256) void sumkron_dw_plain(const float* __restrict_
     const int e = (int)(idx % D);
     const int c = (int)((idx / D) % D);
     const int i = (int)(idx / ((int64_t)D * D));
-    float acc = 0.f;
-    for (int64_t row = 0; row < rows; ++row) acc = fmaf(u[(row * k + i) * D + c], to_float(dy[row * D + e]), acc);
-    dw[idx] = from_float<T_>(acc);
+    double acc = 0.0;  // a sum over the whole batch: fp64 keeps the fp32 result within its last bits
+    for (int64_t row = 0; row < rows; ++row) acc += (double)u[(row * k + i) * D + c] * (double)to_float(dy[row * D + e]);
+    dw[idx] = from_float<T_>((float)acc);
 }
 template <typename T_>
 __global__ __launch_bounds__(256) void sumkron_dz_plain(const T_* __restrict__ x, const float* __restrict__ gq, T_* __restrict__ dz,
@@ -512,10 +513,10 @@ __global__ __launch_bounds__(256) void sumkron_dz_plain(const T_* __restrict__ x
     const int t = (int)(idx % T);
     const int s = (int)((idx / T) % S);
     const int i = (int)(idx / ((int64_t)T * S));
-    float acc = 0.f;
+    double acc = 0.0;  // a sum over the whole batch, as above
     for (int64_t b = 0; b < B; ++b)
-        for (int c = 0; c < D; ++c) acc = fmaf(to_float(x[(b * S + s) * D + c]), gq[(((b * T + t) * k) + i) * D + c], acc);
-    dz[idx] = from_float<T_>(acc);
+        for (int c = 0; c < D; ++c) acc += (double)to_float(x[(b * S + s) * D + c]) * (double)gq[(((b * T + t) * k) + i) * D + c];
+    dz[idx] = from_float<T_>((float)acc);
 }
 
 struct BwdLayout {

@@ -37,10 +37,10 @@ def assert_close(got, ref, tol, what=""):
 
 
 def assert_close_sums(got, ref, tol, what=""):
-    """Criterion for outputs that are sums of many products whose factors were rounded to bf16 on
-    the way (weight gradients: sums over the batch).  The rounding errors of the terms add up like
-    a random walk: their total is about 2^-9 / sqrt(3) times the root of the sum of the squared
-    terms, which is the typical magnitude (RMS) of the outputs themselves, whatever the value of
+    """Criterion for outputs that are sums of many products whose factors were rounded on the way
+    (weight gradients: sums over the batch; the factor is a bf16 or fp32 intermediate).  The rounding
+    errors of the terms add up like a random walk: their total is about the unit roundoff (2^-9 for
+    bf16) / sqrt(3) times the root of the sum of the squared terms, which is the typical magnitude (RMS) of the outputs themselves, whatever the value of
     the one output at hand.  So: |x - r| <= tol (rms(ref) + |r|) for every element.  A misplaced
     or missing operand changes outputs by the order of rms(ref) and fails."""
     got = np.asarray(got, dtype=np.float64)

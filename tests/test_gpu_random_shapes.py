@@ -4,13 +4,14 @@ score functions and windows drawn per case, so that rarely used template paths a
 combinations are exercised.  Scores are kept in the regime where the bf16 rounding of the
 weights stays inside the tolerance (small scale, short histories)."""
 import math
+import os
 
 import numpy as np
 import pytest
 import torch
 
 from paper_2602_10016_amd import workloads as W
-from tests.helpers import TOL, assert_close, assert_lse_close, offsets_dev, to_dev, to_np
+from tests.helpers import TOL, assert_close, assert_close_sums, assert_lse_close, offsets_dev, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -20,6 +21,10 @@ def kb():
     from paper_2602_10016_amd import binding
     assert torch.cuda.is_available()
     return binding
+
+
+# number of drawn cases (KUNLUN_RANDOM_CASES raises it for a longer hunt)
+N_CASES = int(os.environ.get("KUNLUN_RANDOM_CASES", "24"))
 
 
 def _draw(seed):
@@ -42,7 +47,7 @@ def _draw(seed):
                 d_o=bf((q_off[-1], H, d), 1.0), scale=0.4 / math.sqrt(d), rng=rng)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(N_CASES))
 def test_gdpa_forward_backward_random_shapes(kb, oracle, seed):
     c = _draw(seed)
     what = f"seed {seed}: B={c['B']} H={c['H']} d={c['d']} max_q={c['max_q']} max_kv={c['max_kv']} jagged_q={c['jagged_q']} acts={c['acts']}"
@@ -65,7 +70,7 @@ def test_gdpa_forward_backward_random_shapes(kb, oracle, seed):
     assert_close(to_np(dv), dv_ref, TOL["bf16"], what + " dV")
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(max(1, 2 * N_CASES // 3)))
 def test_sliding_window_forward_backward_random_shapes(kb, oracle, seed):
     rng = np.random.default_rng(2000 + seed)
     B = int(rng.integers(1, 6))
@@ -93,3 +98,32 @@ def test_sliding_window_forward_backward_random_shapes(kb, oracle, seed):
     assert_close(to_np(dq), dq_ref, TOL["bf16"], what + " dQ")
     assert_close(to_np(dk), dk_ref, TOL["bf16"], what + " dK")
     assert_close(to_np(dv), dv_ref, TOL["bf16"], what + " dV")
+
+
+@pytest.mark.parametrize("seed", range(max(1, N_CASES // 2)))
+def test_sumkron_forward_backward_random_shapes(kb, oracle, seed):
+    """Shapes on both sides of the conditions of the matrix-core path (D a multiple of 128, S of 32 for
+    the forward; S of 128, T*k and B*T of 32 in addition for the backward) and fp32."""
+    rng = np.random.default_rng(3000 + seed)
+    dtype = "fp32" if rng.integers(5) == 0 else "bf16"
+    B = int(rng.integers(1, 7))
+    S = int(rng.choice([32, 64, 128, 160, 256, 24]))
+    T = int(rng.choice([1, 5, 16, 32, 48]))
+    D = int(rng.choice([128, 256, 384, 40, 24]))
+    k = int(rng.integers(1, 9))
+    draw = lambda shape, s: (rng.standard_normal(shape) * s).astype(np.float32)
+    x, z, w, dy = draw((B, S, D), 1.0), draw((k, S, T), 1 / math.sqrt(S)), draw((k, D, D), 1 / math.sqrt(D)), draw((B, T, D), 1.0)
+    if dtype == "bf16":
+        x, z, w, dy = [W.round_to_bf16(a) for a in (x, z, w, dy)]
+    tol = TOL["bf16"] if dtype == "bf16" else 2e-5
+    what = f"seed {seed}: {dtype} B={B} S={S} T={T} D={D} k={k}"
+    xd, zd, wd, dyd = [to_dev(a, dtype) for a in (x, z, w, dy)]
+    y = kb.sumkron_fwd(xd, zd, wd)
+    dx, dz, dw = kb.sumkron_bwd(xd, zd, wd, dyd)
+    torch.cuda.synchronize()
+    assert_close(to_np(y), oracle.sumkron_fwd(x, z, w), tol, what + " Y")
+    rx, rz, rw = oracle.sumkron_bwd(x, z, w, dy)
+    assert_close(to_np(dx), rx, tol, what + " dX")
+    # sums over the batch of products with a rounded factor (bf16 or fp32 intermediates): error relative to the typical output
+    assert_close_sums(to_np(dz), rz, tol, what + " dZ")
+    assert_close_sums(to_np(dw), rw, tol, what + " dW")
