@@ -378,14 +378,12 @@ static hipError_t launch_bwd(const AttnParams& p, hipStream_t stream) {
     constexpr int bytes = BwdSmem<D, NQB, NW>::TOTAL;
     auto kern = gdpa_bwd_mfma_kernel<D, NQB, NW>;
     if (bytes > 64 * 1024) {
-        // raise the kernel's dynamic LDS limit once per process (not a stream operation, so a
-        // later call under graph capture launches only kernels)
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        // raise the kernel's dynamic LDS limit once per process (initialisation of a function-local
+        // static is thread-safe; not a stream operation, so a later call under graph capture
+        // launches only kernels)
+        static const hipError_t raised =
+            hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (raised != hipSuccess) return raised;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H)), dim3(64 * NW), bytes, stream, p);
     return hipGetLastError();

@@ -346,12 +346,11 @@ __global__ __launch_bounds__(256, 2) void gdpa_bwd_pair_kernel(AttnParams p) {
 
 hipError_t launch_mfma_bwd_pair(const AttnParams& p, hipStream_t stream) {
     constexpr int bytes = PairSmem::TOTAL;
-    static bool raised = false;  // once per process; not a stream operation
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)gdpa_bwd_pair_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    // once per process (initialisation of a function-local static is thread-safe); not a stream operation,
+    // so a later call under graph capture launches only kernels
+    static const hipError_t raised =
+        hipFuncSetAttribute((const void*)gdpa_bwd_pair_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (raised != hipSuccess) return raised;
     hipLaunchKernelGGL(gdpa_bwd_pair_kernel, dim3((unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H)), dim3(256), bytes, stream, p);
     return hipGetLastError();
 }
