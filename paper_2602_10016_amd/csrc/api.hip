@@ -51,7 +51,8 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
         return WS_HEADER_BYTES + tile_table_bytes(B, total_q);
     case KUNLUN_OP_GDPA_BWD:
     case KUNLUN_OP_SWA_BWD:
-        return WS_HEADER_BYTES + order_bytes(B) + mfma_bwd_tiled_workspace(B, H, total_q, total_kv);
+        return WS_HEADER_BYTES + order_bytes(B) +
+               mfma_bwd_tiled_workspace(B, H, d, max_q, max_kv, total_q, total_kv, op == KUNLUN_OP_SWA_BWD);
     default:
         return 0;
     }

@@ -105,6 +105,16 @@ struct UFrag {
     }
 };
 
+#define KUNLUN_ACT_SWITCH(ACTV, CALL)                                   \
+    switch (ACTV) {                                                     \
+    case KUNLUN_ACT_SOFTMAX: { constexpr int A = KUNLUN_ACT_SOFTMAX; CALL; } break;     \
+    case KUNLUN_ACT_IDENTITY: { constexpr int A = KUNLUN_ACT_IDENTITY; CALL; } break;   \
+    case KUNLUN_ACT_RELU: { constexpr int A = KUNLUN_ACT_RELU; CALL; } break;           \
+    case KUNLUN_ACT_GELU: { constexpr int A = KUNLUN_ACT_GELU; CALL; } break;           \
+    case KUNLUN_ACT_GELU_TANH: { constexpr int A = KUNLUN_ACT_GELU_TANH; CALL; } break; \
+    default: { constexpr int A = KUNLUN_ACT_SILU; CALL; } break;                        \
+    }
+
 // ------------------------------------------------------------------ pass A: dQ
 
 template <int D, int NW, int ACT, bool WINDOWED>
@@ -486,15 +496,6 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
 
 // ------------------------------------------------------------------ kernels
 
-#define KUNLUN_ACT_SWITCH(ACTV, CALL)                                   \
-    switch (ACTV) {                                                     \
-    case KUNLUN_ACT_SOFTMAX: { constexpr int A = KUNLUN_ACT_SOFTMAX; CALL; } break;     \
-    case KUNLUN_ACT_IDENTITY: { constexpr int A = KUNLUN_ACT_IDENTITY; CALL; } break;   \
-    case KUNLUN_ACT_RELU: { constexpr int A = KUNLUN_ACT_RELU; CALL; } break;           \
-    case KUNLUN_ACT_GELU: { constexpr int A = KUNLUN_ACT_GELU; CALL; } break;           \
-    case KUNLUN_ACT_GELU_TANH: { constexpr int A = KUNLUN_ACT_GELU_TANH; CALL; } break; \
-    default: { constexpr int A = KUNLUN_ACT_SILU; CALL; } break;                        \
-    }
 
 // work mapping of tile_map.h in both passes
 template <int D, int NW, bool WINDOWED>
@@ -562,12 +563,286 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t* __restrict__ o
     }
 }
 
+// ------------------------------------------------------------------ few keys: one pass
+//
+// The PFFN direction proper: long query sequences, at most 32 keys per example (the context
+// tokens).  With a single key tile there is no key loop and nothing to accumulate across tiles,
+// so one workgroup per (example, 128-query tile, head) does all five contractions in one pass over
+// Q and dO: per wave (32 queries)
+//     S^T = K Q^T,  dP^T = V dO^T,  P^T / dS^T in registers  ->  dQ^T = K^T dS^T  (stored at once)
+//     P, dS through a 2 KB LDS tile each (query-per-lane -> key-per-lane)
+//     dV^T = dO^T P,  dK^T = Q^T dS  over the wave's 32 queries
+// The dK / dV contributions of the four waves are added in LDS (fixed order) and written as one fp32
+// partial tile per workgroup; a second kernel adds the partial tiles of an example in tile order
+// (bit-reproducible, no atomics) and rounds once.  Against the two-pass kernels this reads Q and dO
+// once instead of twice and keeps all four waves busy.
+
+template <int D>
+struct FewKeysSmem {
+    using PT = PadTiles<D>;
+    static constexpr int TILE = KT * D * 2;       // 32 rows of D bf16, two-way swizzle
+    static constexpr int P_BYTES = KT * 64;       // [query][key] bf16, 64 bytes per row
+    static constexpr int WAVE = 2 * TILE;         // a wave's Q and dO tiles; later its partial sums, last its dQ staging rows
+    // K and V tiles first; once every wave has finished its reads of them, the P / dS tiles of the four waves
+    // take their place (d = 32: the K / V tiles are smaller than that, the region is sized for the larger use)
+    static constexpr int HEAD = 2 * TILE > 8 * P_BYTES ? 2 * TILE : 8 * P_BYTES;
+    static constexpr int TOTAL = HEAD + 4 * WAVE;
+    static constexpr int PART = KT * D * 4;       // a wave's fp32 [key][channel] partial sums
+    static_assert(PART <= WAVE, "a wave's partial sums go into its dead Q and dO tiles");
+    static_assert(PT::ROW_TILE <= WAVE, "and so do its dQ staging rows");
+};
+
+inline size_t fewkeys_partial_bytes(int B, int H, int d, int64_t total_q) {
+    return align_up((size_t)(total_q / TILE_ROWS + B) * H * 2 * KT * d * sizeof(float), 256);
+}
+inline bool fewkeys_applies(int d, int max_q, int max_kv, bool windowed) {
+    return !windowed && max_q > 64 && max_kv <= KT && (d == 32 || d == 64 || d == 128);
+}
+
+// P / dS tile: row = query, 4 chunks of 16 bytes (8 keys) per row, chunk index swizzled by the row.
+__device__ __forceinline__ int pq_offset(int row, int byte_in_row) {
+    return row * 64 + ((((byte_in_row >> 4) ^ (row >> 2)) & 3) << 4) + (byte_in_row & 15);
+}
+// fp32 [key][channel] partial sums: 16-byte chunks swizzled by the row.
+template <int D>
+__device__ __forceinline__ int part_offset(int row, int chunk) {
+    return row * D * 4 + ((chunk ^ (row & (D / 4 - 1))) << 4);
+}
+
+template <int D, int ACT>
+__device__ __forceinline__ void bwd_fewkeys_item(const AttnParams& p, const float* __restrict__ delta_ws, char* lds, int h,
+                                                 int64_t q_row0, int nq_wg, int64_t k0, int n_kv,
+                                                 float* __restrict__ part_out) {
+    using L = TileLayout<D>;
+    using SM = FewKeysSmem<D>;
+    constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
+    constexpr int KC = D / 16, DB = D / 32;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 31, g = lane >> 5;
+    const int64_t hd = (int64_t)p.H * D;
+    const uint32_t row_bytes = (uint32_t)(hd * 2);
+    char* ldsK = lds;
+    char* ldsV = lds + SM::TILE;
+    char* wbase = lds + SM::HEAD + wave * SM::WAVE;
+    char* ldsQ = wbase;
+    char* ldsDO = wbase + SM::TILE;
+    char* ldsP = lds + wave * 2 * SM::P_BYTES;  // over the K / V tiles, once those are dead
+    char* ldsDS = ldsP + SM::P_BYTES;
+
+    const int q_lo_w = wave * 32;
+    int nq = nq_wg - q_lo_w;
+    nq = nq < 0 ? 0 : (nq > 32 ? 32 : nq);
+
+    // ---- staging: whole rows, 16 bytes per lane, rows past the end read as zero (buffer range).
+    // K and V by the whole workgroup, Q and dO of a wave's 32 queries by that wave.
+    {
+        constexpr int CHUNKS = D / 8;
+        const u32x4 zero = {0, 0, 0, 0};
+        for (int idx = tid; idx < KT * CHUNKS; idx += 256) {
+            const int row = idx / CHUNKS, ch = idx % CHUNKS;
+            u32x4 kv = zero, vv = zero;
+            if (row < n_kv) {
+                kv = *(const u32x4*)((const bf16_t*)p.k + (k0 + row) * hd + (int64_t)h * D + ch * 8);
+                vv = *(const u32x4*)((const bf16_t*)p.v + (k0 + row) * hd + (int64_t)h * D + ch * 8);
+            }
+            *(u32x4*)(ldsK + L::u_offset(row, ch * 16)) = kv;
+            *(u32x4*)(ldsV + L::u_offset(row, ch * 16)) = vv;
+        }
+        const bf16_t* Qg = (const bf16_t*)p.q + (q_row0 + q_lo_w) * hd + (int64_t)h * D;
+        const bf16_t* DOg = (const bf16_t*)p.d_o + (q_row0 + q_lo_w) * hd + (int64_t)h * D;
+        u32x4 qs[L::LOADS], ds[L::LOADS];
+        const int chunk = lane % CHUNKS, rsub = lane / CHUNKS;
+#pragma unroll
+        for (int i = 0; i < L::LOADS; ++i) {
+            const int row = i * L::ROWS_PER_LOAD + rsub;
+            qs[i] = zero; ds[i] = zero;
+            if (row < nq) {
+                qs[i] = __builtin_nontemporal_load((const u32x4*)(Qg + row * hd + chunk * 8));
+                ds[i] = __builtin_nontemporal_load((const u32x4*)(DOg + row * hd + chunk * 8));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < L::LOADS; ++i) {
+            const int row = i * L::ROWS_PER_LOAD + rsub;
+            *(u32x4*)(ldsQ + L::u_offset(row, chunk * 16)) = qs[i];
+            *(u32x4*)(ldsDO + L::u_offset(row, chunk * 16)) = ds[i];
+        }
+    }
+    // softmax statistics of this lane's query
+    float lse2 = INFINITY, delta = 0.f;
+    if (SOFTMAX && r < nq) {
+        const int64_t idx = (int64_t)h * p.total_q + q_row0 + q_lo_w + r;
+        lse2 = p.lse[idx] * LOG2E_T;
+        delta = delta_ws[idx];
+    }
+    __syncthreads();
+
+    UFrag<D> uf;
+    uf.init(lane);
+    const float sc = SOFTMAX ? p.scale * LOG2E_T : p.scale;
+    const int s16 = lane & 15, hi16 = (lane >> 4) & 1;
+
+    // ---- S^T = K Q^T and dP^T = V dO^T: lane = query r of the wave, registers = keys
+    f32x16 sacc, dpacc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+        sacc = mfma32(uf.row(ldsK, kc), uf.row(ldsQ, kc), sacc);
+        dpacc = mfma32(uf.row(ldsV, kc), uf.row(ldsDO, kc), dpacc);
+    }
+    // ---- P^T, dS^T; keys past the end of the example's keys get zero weight (padding queries have zero
+    // Q and dO rows: their P = f(0) = 0 in every activation mode, softmax lanes have lse = +inf)
+    float pv[16], dsv[16];
+    const unsigned keys_left = (unsigned)(n_kv - 4 * g);  // key 8*(v/4) + (v%4) + 4g < n_kv
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const float s = sacc[v] * sc;
+        if (SOFTMAX) {
+            pv[v] = fast_exp2(s - lse2);
+            dsv[v] = pv[v] * (dpacc[v] - delta) * p.scale;
+        } else {
+            float der;
+            act_fast_vd<ACT>(s, pv[v], der);
+            dsv[v] = dpacc[v] * der * p.scale;
+        }
+        const bool ok = n_kv > 4 * g && (unsigned)(8 * (v >> 2) + (v & 3)) < keys_left;
+        pv[v] = ok ? pv[v] : 0.f;
+        dsv[v] = ok ? dsv[v] : 0.f;
+    }
+    bf16x8 dsf[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dsf[c][e] = (bf16_t)dsv[8 * c + e];
+    // ---- dQ^T = K^T dS^T; kept in registers until the LDS is free for the transposition to rows
+    f32x16 dqacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) dqacc[db] = mfma32(uf.transposed(ldsK, db, c), dsf[c], dqacc[db]);
+    }
+    __syncthreads();  // every wave is done with the K and V tiles: the P / dS tiles take their place
+    // registers 4*vg .. 4*vg+3 hold keys 8*vg + 4g + 0..3 of query r
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg) {
+        bf16x4 pk, dk4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { pk[e] = (bf16_t)pv[4 * vg + e]; dk4[e] = (bf16_t)dsv[4 * vg + e]; }
+        *(bf16x4*)(ldsP + pq_offset(r, (8 * vg + 4 * g) * 2)) = pk;
+        *(bf16x4*)(ldsDS + pq_offset(r, (8 * vg + 4 * g) * 2)) = dk4;
+    }
+    // ---- dV^T = dO^T P and dK^T = Q^T dS over the wave's 32 queries: lane = key r, registers = channels.
+    // P and dS come back from LDS as B operands (column = key, contraction over 16 queries per step).
+    const int ptA = pq_offset(8 * g + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);
+    const int ptB = pq_offset(8 * g + 4 + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);
+    bf16x8 pb[2], dsb[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        pb[j] = tr_pair(ldsP + j * 16 * 64 + ptA, ldsP + j * 16 * 64 + ptB);
+        dsb[j] = tr_pair(ldsDS + j * 16 * 64 + ptA, ldsDS + j * 16 * 64 + ptB);
+    }
+    // A operands (row = channel, contraction = queries 16j + 8g + 0..7): transposing reads of the dO / Q tiles
+    int qtA[DB], qtB[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        const int colb = (32 * db + 16 * hi16 + 4 * (s16 & 3)) * 2;
+        qtA[db] = L::u_offset(8 * g + (s16 >> 2), colb);
+        qtB[db] = L::u_offset(8 * g + 4 + (s16 >> 2), colb);
+    }
+    f32x16 dvacc[DB], dkacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { dvacc[db][v] = 0.f; dkacc[db][v] = 0.f; }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int ro = j * 16 * L::ROW_BYTES;
+            dvacc[db] = mfma32(tr_pair(ldsDO + ro + qtA[db], ldsDO + ro + qtB[db]), pb[j], dvacc[db]);
+            dkacc[db] = mfma32(tr_pair(ldsQ + ro + qtA[db], ldsQ + ro + qtB[db]), dsb[j], dkacc[db]);
+        }
+    }
+    // ---- the four waves' contributions are added in LDS, dV first, then dK.  A wave's partial sums go
+    // into its own Q / dO tiles, which only that wave has read.
+    char* mine = ldsQ;
+    const int n_chunks = KT * D / 4;  // 16-byte chunks of a [32][D] fp32 tile
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                f32x4 x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[e] = which == 0 ? dvacc[db][4 * vg + e] : dkacc[db][4 * vg + e];
+                *(f32x4*)(mine + part_offset<D>(r, (32 * db + 8 * vg + 4 * g) / 4)) = x;
+            }
+        __syncthreads();
+        float* dst = part_out + (size_t)which * KT * D;
+        for (int idx = tid; idx < n_chunks; idx += 256) {
+            const int row = idx / (D / 4), ch = idx % (D / 4);
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sum += *(const f32x4*)(lds + SM::HEAD + w * SM::WAVE + part_offset<D>(row, ch));
+            *(f32x4*)(dst + row * D + ch * 4) = sum;
+        }
+        __syncthreads();  // the partial tiles are rewritten: for dK, then as dQ staging rows
+    }
+    if (nq > 0) store_tile_rows<D>(mine, dqacc, (bf16_t*)p.dq + (q_row0 + q_lo_w) * hd + (int64_t)h * D, hd, nq, lane);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void bwd_fewkeys_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+                                                          const int32_t* __restrict__ tile_example,
+                                                          const float* __restrict__ delta_ws, float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(1024))) char fk_lds[];
+    int b, h, qt;
+    if (!locate_tile(tile_start, tile_example, p.B, p.H, 1, b, h, qt)) return;
+    const int64_t k0 = p.kv_off[b];
+    int n_kv = p.kv_off[b + 1] - (int)k0;
+    n_kv = n_kv > KT ? KT : n_kv;  // the launch condition (max_kv <= 32) promises this; never read past the tile
+    const int64_t q0 = q_begin(p, b);
+    const int nq_all = (int)(q_end(p, b) - q0);
+    const int q_first = qt * TILE_ROWS;
+    const int nq = (nq_all - q_first) < TILE_ROWS ? (nq_all - q_first) : TILE_ROWS;
+    float* part_out = partial + ((size_t)(tile_start[b] + qt) * p.H + h) * (2 * KT * D);
+    KUNLUN_ACT_SWITCH(p.head_act[h], (bwd_fewkeys_item<D, A>(p, delta_ws, fk_lds, h, q0 + q_first, nq, k0, n_kv, part_out)));
+}
+
+// dK, dV rows of every example = sum of the partial tiles of its query tiles, in tile order; 4 channels per thread.
+template <int D>
+__global__ __launch_bounds__(256) void fewkeys_reduce_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+                                                             const float* __restrict__ partial) {
+    constexpr int PER_ROW = D / 4;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (((b*H + h)*2 + which)*32 + key)*PER_ROW + c4
+    if (gid >= (int64_t)p.B * p.H * 2 * KT * PER_ROW) return;
+    const int c4 = (int)(gid % PER_ROW);
+    const int key = (int)((gid / PER_ROW) % KT);
+    const int which = (int)((gid / (PER_ROW * KT)) % 2);
+    const int h = (int)((gid / (PER_ROW * KT * 2)) % p.H);
+    const int b = (int)(gid / ((int64_t)PER_ROW * KT * 2 * p.H));
+    const int64_t k0 = p.kv_off[b];
+    if (key >= p.kv_off[b + 1] - (int)k0) return;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int t = tile_start[b]; t < tile_start[b + 1]; ++t)
+        sum += *(const f32x4*)(partial + (((size_t)t * p.H + h) * 2 + which) * (KT * D) + key * D + c4 * 4);
+    bf16x4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = (bf16_t)sum[e];
+    bf16_t* dst = (bf16_t*)(which == 0 ? p.dv : p.dk) + (k0 + key) * (int64_t)p.H * D + (int64_t)h * D + c4 * 4;
+    *(bf16x4*)dst = out;
+}
+
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype) {
     return dtype == KUNLUN_BF16 && (p.d == 32 || p.d == 64 || p.d == 128);
 }
 
-size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv) {
-    return tile_table_bytes(B, total_q) + tile_table_bytes(B, total_kv) + align_up((size_t)H * total_q * sizeof(float), 256);
+size_t mfma_bwd_tiled_workspace(int B, int H, int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, bool windowed) {
+    return tile_table_bytes(B, total_q) + tile_table_bytes(B, total_kv) + align_up((size_t)H * total_q * sizeof(float), 256) +
+           (fewkeys_applies(d, max_q, max_kv, windowed) ? fewkeys_partial_bytes(B, H, d, total_q) : 0);
 }
 
 template <int D, bool WINDOWED>
@@ -597,8 +872,41 @@ static hipError_t launch_tiled(const AttnParams& p, char* ws, bool any_softmax, 
     return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_fewkeys(const AttnParams& p, char* ws, bool any_softmax, hipStream_t stream) {
+    int32_t* q_tiles = (int32_t*)ws;
+    float* delta = (float*)(ws + tile_table_bytes(p.B, p.total_q) + tile_table_bytes(p.B, p.total_kv));
+    float* partial = (float*)((char*)delta + align_up((size_t)p.H * p.total_q * sizeof(float), 256));
+    constexpr int bytes = FewKeysSmem<D>::TOTAL;
+    if (bytes > 64 * 1024) {
+        // once per process (thread-safe initialisation of a function-local static); not a stream operation
+        static const hipError_t raised =
+            hipFuncSetAttribute((const void*)bwd_fewkeys_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (raised != hipSuccess) return raised;
+    }
+    if (any_softmax && p.total_q > 0) {
+        const int64_t threads = p.total_q * p.H * (D / 8);
+        hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                           (const bf16_t*)p.o, (const bf16_t*)p.d_o, delta, p.total_q, p.H);
+    }
+    hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, q_tiles,
+                       tile_example_of(q_tiles, p.B));
+    if (p.total_q > 0)
+        hipLaunchKernelGGL((bwd_fewkeys_kernel<D>), dim3(tile_grid(p.B, p.H, p.total_q, 1)), dim3(256), bytes, stream, p, q_tiles,
+                           tile_example_of(q_tiles, p.B), delta, partial);
+    if (p.total_kv > 0) {
+        const int64_t threads = (int64_t)p.B * p.H * 2 * KT * (D / 4);
+        hipLaunchKernelGGL((fewkeys_reduce_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, p, q_tiles,
+                           partial);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool any_softmax, hipStream_t stream) {
     char* ws = (char*)workspace_tail;
+    if (fewkeys_applies(p.d, p.max_q, p.max_kv, p.windowed != 0))
+        return p.d == 128 ? launch_fewkeys<128>(p, ws, any_softmax, stream)
+               : p.d == 64 ? launch_fewkeys<64>(p, ws, any_softmax, stream) : launch_fewkeys<32>(p, ws, any_softmax, stream);
     if (p.windowed)
         return p.d == 128 ? launch_tiled<128, true>(p, ws, true, stream)
                : p.d == 64 ? launch_tiled<64, true>(p, ws, true, stream) : launch_tiled<32, true>(p, ws, true, stream);

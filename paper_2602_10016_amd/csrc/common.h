@@ -56,7 +56,7 @@ size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
 hipError_t launch_mfma_bwd_pair(const AttnParams& p, hipStream_t stream);
 // Two-pass matrix-core backward (sliding window, or more than 64 queries per example).
 bool mfma_bwd_tiled_supported(const AttnParams& p, int dtype);
-size_t mfma_bwd_tiled_workspace(int B, int H, int64_t total_q, int64_t total_kv);
+size_t mfma_bwd_tiled_workspace(int B, int H, int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, bool windowed);
 hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool any_softmax, hipStream_t stream);
 
 // SumKronLinear (two tiled GEMMs with a bf16 intermediate, or plain fp32 kernels)

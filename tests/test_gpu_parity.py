@@ -411,6 +411,27 @@ def test_backward_long_jagged_queries_few_keys(kb, oracle, d, act):
     check_gdpa_bwd(kb, oracle, wl, ACTS[act])
 
 
+@pytest.mark.parametrize("d", [32, 64, 128])
+@pytest.mark.parametrize("act", list(ACTS))
+def test_backward_long_jagged_queries_at_most_32_keys(kb, oracle, d, act):
+    """The PFFN direction proper (every example has at most 32 keys): the one-pass backward with
+    per-tile partial sums of dK / dV.  Examples with no key, one key, a full tile, no query."""
+    rng = np.random.default_rng(41)
+    H = 3
+    lens_q = np.array([300, 1, 0, 128, 129, 65, 257, 90, 640])
+    lens_kv = np.array([16, 32, 8, 0, 31, 1, 32, 5, 24])
+    B = len(lens_q)
+    wl = W.make("cfg5", 42, B=B, H=H, d=d, Nq=1, lengths=("list", lens_kv), scale=0.5 / math.sqrt(d))
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.d_o = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32))
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = int(lens_q.max())
+    check_gdpa_bwd(kb, oracle, wl, ACTS[act])
+    if act == "gelu":
+        check_gdpa_bwd(kb, oracle, wl, 0, head_act=[0, 5, 3])
+
+
 def test_backward_dense_long_queries_per_head(kb, oracle):
     wl = W.make("cfg5", 33, B=4, H=6, d=128, Nq=150, lengths=("list", [40, 0, 64, 7]), scale=0.5 / math.sqrt(128))
     check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4])
