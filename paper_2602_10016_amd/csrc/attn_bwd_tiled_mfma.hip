@@ -40,20 +40,21 @@ struct PadTiles {
 // registers: channels 32*db + 8*(v/4) + 4g + v%4) -> bf16 rows of a [tokens, H, D] tensor,
 // transposed through the wave's own LDS region and written 16 bytes per lane.
 template <int D>
-__device__ __forceinline__ void store_tile_rows(char* stage, const f32x16 (&acc)[D / 32], bf16_t* out_rows, int64_t hd,
-                                                int n_rows, int lane) {
+__device__ __forceinline__ void store_block_staged(char* stage, const f32x16& acc, int db, int lane) {
     using PT = PadTiles<D>;
-    constexpr int CHUNKS = D / 8;
     const int r = lane & 31, g = lane >> 5;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int vg = 0; vg < 4; ++vg) {
+        bf16x4 out;
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-            bf16x4 out;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) out[e] = (bf16_t)acc[db][4 * vg + e];
-            *(bf16x4*)(stage + r * PT::ROW_STRIDE + (32 * db + 8 * vg + 4 * g) * 2) = out;
-        }
+        for (int e = 0; e < 4; ++e) out[e] = (bf16_t)acc[4 * vg + e];
+        *(bf16x4*)(stage + r * PT::ROW_STRIDE + (32 * db + 8 * vg + 4 * g) * 2) = out;
+    }
+}
+template <int D>
+__device__ __forceinline__ void store_staged_rows(const char* stage, bf16_t* out_rows, int64_t hd, int n_rows, int lane) {
+    using PT = PadTiles<D>;
+    constexpr int CHUNKS = D / 8;
     const int chunk = lane % CHUNKS, rsub = lane / CHUNKS;
 #pragma unroll
     for (int i = 0; i < 32 * CHUNKS / 64; ++i) {
@@ -61,6 +62,13 @@ __device__ __forceinline__ void store_tile_rows(char* stage, const f32x16 (&acc)
         const u32x4 val = *(const u32x4*)(stage + row * PT::ROW_STRIDE + chunk * 16);
         if (row < n_rows) __builtin_nontemporal_store(val, (u32x4*)(out_rows + row * hd + chunk * 8));
     }
+}
+template <int D>
+__device__ __forceinline__ void store_tile_rows(char* stage, const f32x16 (&acc)[D / 32], bf16_t* out_rows, int64_t hd,
+                                                int n_rows, int lane) {
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) store_block_staged<D>(stage, acc[db], db, lane);
+    store_staged_rows<D>(stage, out_rows, hd, n_rows, lane);
 }
 
 // One 8-element fragment from two transposing reads (rows .. +3 at a, rows .. +3 at b).
@@ -582,18 +590,26 @@ struct FewKeysSmem {
     using PT = PadTiles<D>;
     static constexpr int TILE = KT * D * 2;       // 32 rows of D bf16, two-way swizzle
     static constexpr int P_BYTES = KT * 64;       // [query][key] bf16, 64 bytes per row
-    static constexpr int WAVE = 2 * TILE;         // a wave's Q and dO tiles; later its partial sums, last its dQ staging rows
-    // K and V tiles first; once every wave has finished its reads of them, the P / dS tiles of the four waves
-    // take their place (d = 32: the K / V tiles are smaller than that, the region is sized for the larger use)
-    static constexpr int HEAD = 2 * TILE > 8 * P_BYTES ? 2 * TILE : 8 * P_BYTES;
+    static constexpr int WAVE = 2 * TILE;         // a wave's Q and dO tiles; later its dQ staging rows, last its partial sums
+    // K tile, then the V tile; once every wave has finished its reads of V, the P (then dS) tiles of the four
+    // waves take its place (d < 128: the V tile is smaller than that, the region is sized for the larger use)
+    static constexpr int V_REGION = TILE > 4 * P_BYTES ? TILE : 4 * P_BYTES;
+    static constexpr int HEAD = TILE + V_REGION;
     static constexpr int TOTAL = HEAD + 4 * WAVE;
     static constexpr int PART = KT * D * 4;       // a wave's fp32 [key][channel] partial sums
     static_assert(PART <= WAVE, "a wave's partial sums go into its dead Q and dO tiles");
     static_assert(PT::ROW_TILE <= WAVE, "and so do its dQ staging rows");
 };
 
+// Query tiles that one workgroup walks (accumulating dK / dV in registers): more tiles mean fewer
+// partial sums to write and read back, fewer workgroups mean an emptier machine.
+inline int fewkeys_chunk_tiles(int B, int H, int64_t total_q) {
+    const int64_t wgs = (total_q / TILE_ROWS + B) * H;
+    return wgs >= 16384 ? 8 : (wgs >= 4096 ? 4 : (wgs >= 2048 ? 2 : 1));
+}
 inline size_t fewkeys_partial_bytes(int B, int H, int d, int64_t total_q) {
-    return align_up((size_t)(total_q / TILE_ROWS + B) * H * 2 * KT * d * sizeof(float), 256);
+    const int chunk_rows = TILE_ROWS * fewkeys_chunk_tiles(B, H, total_q);
+    return align_up((size_t)(total_q / chunk_rows + B) * H * 2 * KT * d * sizeof(float), 256);
 }
 inline bool fewkeys_applies(int d, int max_q, int max_kv, bool windowed) {
     return !windowed && max_q > 64 && max_kv <= KT && (d == 32 || d == 64 || d == 128);
@@ -611,141 +627,33 @@ __device__ __forceinline__ int part_offset(int row, int chunk) {
 
 template <int D, int ACT>
 __device__ __forceinline__ void bwd_fewkeys_item(const AttnParams& p, const float* __restrict__ delta_ws, char* lds, int h,
-                                                 int64_t q_row0, int nq_wg, int64_t k0, int n_kv,
+                                                 int64_t q_row0, int nq_chunk, int64_t k0, int n_kv,
                                                  float* __restrict__ part_out) {
     using L = TileLayout<D>;
     using SM = FewKeysSmem<D>;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16, DB = D / 32;
+    constexpr int CHUNKS = D / 8;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
-    const uint32_t row_bytes = (uint32_t)(hd * 2);
     char* ldsK = lds;
     char* ldsV = lds + SM::TILE;
     char* wbase = lds + SM::HEAD + wave * SM::WAVE;
     char* ldsQ = wbase;
     char* ldsDO = wbase + SM::TILE;
-    char* ldsP = lds + wave * 2 * SM::P_BYTES;  // over the K / V tiles, once those are dead
-    char* ldsDS = ldsP + SM::P_BYTES;
-
+    char* ldsP = ldsV + wave * SM::P_BYTES;  // over the V tile, once that is dead: P first, then dS
     const int q_lo_w = wave * 32;
-    int nq = nq_wg - q_lo_w;
-    nq = nq < 0 ? 0 : (nq > 32 ? 32 : nq);
-
-    // ---- staging: whole rows, 16 bytes per lane, rows past the end read as zero (buffer range).
-    // K and V by the whole workgroup, Q and dO of a wave's 32 queries by that wave.
-    {
-        constexpr int CHUNKS = D / 8;
-        const u32x4 zero = {0, 0, 0, 0};
-        for (int idx = tid; idx < KT * CHUNKS; idx += 256) {
-            const int row = idx / CHUNKS, ch = idx % CHUNKS;
-            u32x4 kv = zero, vv = zero;
-            if (row < n_kv) {
-                kv = *(const u32x4*)((const bf16_t*)p.k + (k0 + row) * hd + (int64_t)h * D + ch * 8);
-                vv = *(const u32x4*)((const bf16_t*)p.v + (k0 + row) * hd + (int64_t)h * D + ch * 8);
-            }
-            *(u32x4*)(ldsK + L::u_offset(row, ch * 16)) = kv;
-            *(u32x4*)(ldsV + L::u_offset(row, ch * 16)) = vv;
-        }
-        const bf16_t* Qg = (const bf16_t*)p.q + (q_row0 + q_lo_w) * hd + (int64_t)h * D;
-        const bf16_t* DOg = (const bf16_t*)p.d_o + (q_row0 + q_lo_w) * hd + (int64_t)h * D;
-        u32x4 qs[L::LOADS], ds[L::LOADS];
-        const int chunk = lane % CHUNKS, rsub = lane / CHUNKS;
-#pragma unroll
-        for (int i = 0; i < L::LOADS; ++i) {
-            const int row = i * L::ROWS_PER_LOAD + rsub;
-            qs[i] = zero; ds[i] = zero;
-            if (row < nq) {
-                qs[i] = __builtin_nontemporal_load((const u32x4*)(Qg + row * hd + chunk * 8));
-                ds[i] = __builtin_nontemporal_load((const u32x4*)(DOg + row * hd + chunk * 8));
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < L::LOADS; ++i) {
-            const int row = i * L::ROWS_PER_LOAD + rsub;
-            *(u32x4*)(ldsQ + L::u_offset(row, chunk * 16)) = qs[i];
-            *(u32x4*)(ldsDO + L::u_offset(row, chunk * 16)) = ds[i];
-        }
-    }
-    // softmax statistics of this lane's query
-    float lse2 = INFINITY, delta = 0.f;
-    if (SOFTMAX && r < nq) {
-        const int64_t idx = (int64_t)h * p.total_q + q_row0 + q_lo_w + r;
-        lse2 = p.lse[idx] * LOG2E_T;
-        delta = delta_ws[idx];
-    }
-    __syncthreads();
 
     UFrag<D> uf;
     uf.init(lane);
     const float sc = SOFTMAX ? p.scale * LOG2E_T : p.scale;
     const int s16 = lane & 15, hi16 = (lane >> 4) & 1;
-
-    // ---- S^T = K Q^T and dP^T = V dO^T: lane = query r of the wave, registers = keys
-    f32x16 sacc, dpacc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dpacc[v] = 0.f; }
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-        sacc = mfma32(uf.row(ldsK, kc), uf.row(ldsQ, kc), sacc);
-        dpacc = mfma32(uf.row(ldsV, kc), uf.row(ldsDO, kc), dpacc);
-    }
-    // ---- P^T, dS^T; keys past the end of the example's keys get zero weight (padding queries have zero
-    // Q and dO rows: their P = f(0) = 0 in every activation mode, softmax lanes have lse = +inf)
-    float pv[16], dsv[16];
-    const unsigned keys_left = (unsigned)(n_kv - 4 * g);  // key 8*(v/4) + (v%4) + 4g < n_kv
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const float s = sacc[v] * sc;
-        if (SOFTMAX) {
-            pv[v] = fast_exp2(s - lse2);
-            dsv[v] = pv[v] * (dpacc[v] - delta) * p.scale;
-        } else {
-            float der;
-            act_fast_vd<ACT>(s, pv[v], der);
-            dsv[v] = dpacc[v] * der * p.scale;
-        }
-        const bool ok = n_kv > 4 * g && (unsigned)(8 * (v >> 2) + (v & 3)) < keys_left;
-        pv[v] = ok ? pv[v] : 0.f;
-        dsv[v] = ok ? dsv[v] : 0.f;
-    }
-    bf16x8 dsf[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dsf[c][e] = (bf16_t)dsv[8 * c + e];
-    // ---- dQ^T = K^T dS^T; kept in registers until the LDS is free for the transposition to rows
-    f32x16 dqacc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) dqacc[db][v] = 0.f;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) dqacc[db] = mfma32(uf.transposed(ldsK, db, c), dsf[c], dqacc[db]);
-    }
-    __syncthreads();  // every wave is done with the K and V tiles: the P / dS tiles take their place
-    // registers 4*vg .. 4*vg+3 hold keys 8*vg + 4g + 0..3 of query r
-#pragma unroll
-    for (int vg = 0; vg < 4; ++vg) {
-        bf16x4 pk, dk4;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { pk[e] = (bf16_t)pv[4 * vg + e]; dk4[e] = (bf16_t)dsv[4 * vg + e]; }
-        *(bf16x4*)(ldsP + pq_offset(r, (8 * vg + 4 * g) * 2)) = pk;
-        *(bf16x4*)(ldsDS + pq_offset(r, (8 * vg + 4 * g) * 2)) = dk4;
-    }
-    // ---- dV^T = dO^T P and dK^T = Q^T dS over the wave's 32 queries: lane = key r, registers = channels.
-    // P and dS come back from LDS as B operands (column = key, contraction over 16 queries per step).
     const int ptA = pq_offset(8 * g + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);
     const int ptB = pq_offset(8 * g + 4 + (s16 >> 2), (16 * hi16 + 4 * (s16 & 3)) * 2);
-    bf16x8 pb[2], dsb[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        pb[j] = tr_pair(ldsP + j * 16 * 64 + ptA, ldsP + j * 16 * 64 + ptB);
-        dsb[j] = tr_pair(ldsDS + j * 16 * 64 + ptA, ldsDS + j * 16 * 64 + ptB);
-    }
-    // A operands (row = channel, contraction = queries 16j + 8g + 0..7): transposing reads of the dO / Q tiles
+    // A operands of the last two contractions (row = channel, contraction = queries 16j + 8g + 0..7):
+    // transposing reads of the dO / Q tiles
     int qtA[DB], qtB[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
@@ -753,20 +661,136 @@ __device__ __forceinline__ void bwd_fewkeys_item(const AttnParams& p, const floa
         qtA[db] = L::u_offset(8 * g + (s16 >> 2), colb);
         qtB[db] = L::u_offset(8 * g + 4 + (s16 >> 2), colb);
     }
-    f32x16 dvacc[DB], dkacc[DB];
+    const unsigned keys_left = (unsigned)(n_kv - 4 * g);  // key 8*(v/4) + (v%4) + 4g < n_kv
+
+    f32x16 dvacc[DB], dkacc[DB];  // lane = key r, registers = channels; summed over all tiles of the chunk
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dvacc[db][v] = 0.f; dkacc[db][v] = 0.f; }
+
+    TileDma<D, 1, SWZ_U> dma;  // a wave loads its own tiles
+    dma.init(lane, 0, (uint32_t)(hd * 2));
+    const int n_tiles = (nq_chunk + TILE_ROWS - 1) / TILE_ROWS;
+    for (int it = 0; it < n_tiles; ++it) {
+        const int64_t rows0 = q_row0 + (int64_t)it * TILE_ROWS + q_lo_w;  // first query row of this wave
+        int nq = nq_chunk - it * TILE_ROWS - q_lo_w;
+        nq = nq < 0 ? 0 : (nq > 32 ? 32 : nq);
+        if (it > 0) __syncthreads();  // every wave is done with the P / dS tiles of the previous tile (they lie over V)
+        // ---- staging: whole rows, 16 bytes per lane, rows past the end are zero.  K (once) and V (for every
+        // tile: it was overwritten) by the whole workgroup, Q and dO of a wave's 32 queries by that wave.
+        {
+            const u32x4 zero = {0, 0, 0, 0};
+            for (int idx = tid; idx < KT * CHUNKS; idx += 256) {
+                const int row = idx / CHUNKS, ch = idx % CHUNKS;
+                u32x4 kv = zero, vv = zero;
+                if (row < n_kv) {
+                    if (it == 0) kv = *(const u32x4*)((const bf16_t*)p.k + (k0 + row) * hd + (int64_t)h * D + ch * 8);
+                    vv = *(const u32x4*)((const bf16_t*)p.v + (k0 + row) * hd + (int64_t)h * D + ch * 8);
+                }
+                if (it == 0) *(u32x4*)(ldsK + L::u_offset(row, ch * 16)) = kv;
+                *(u32x4*)(ldsV + L::u_offset(row, ch * 16)) = vv;
+            }
+            // Q and dO straight into LDS (no staging registers); rows past the wave's queries repeat the last
+            // one and get zero weight below; a wave without queries loads nothing and computes nothing
+            if (nq > 0) {
+                dma.issue((const char*)((const bf16_t*)p.q + rows0 * hd + (int64_t)h * D), nq, lds_address(ldsQ));
+                dma.issue((const char*)((const bf16_t*)p.d_o + rows0 * hd + (int64_t)h * D), nq, lds_address(ldsDO));
+            }
+        }
+        // softmax statistics of this lane's query
+        float lse2 = INFINITY, delta = 0.f;
+        if (SOFTMAX && r < nq) {
+            const int64_t idx = (int64_t)h * p.total_q + rows0 + r;
+            lse2 = p.lse[idx] * LOG2E_T;
+            delta = delta_ws[idx];
+        }
+        wait_vmcnt<0>();  // the loads into LDS are not tracked by the compiler
+        __syncthreads();
+        const bool wave_active = nq > 0;
+
+        // packed P^T and dS^T in the register order of the C layout: element e of block c = key 16c + 8(e/4) + 4g + e%4
+        bf16x8 pf[2], dsf[2];
+        if (wave_active) {
+            // ---- S^T = K Q^T and dP^T = V dO^T: lane = query r of the wave, registers = keys
+            f32x16 sacc, dpacc;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int ro = j * 16 * L::ROW_BYTES;
-            dvacc[db] = mfma32(tr_pair(ldsDO + ro + qtA[db], ldsDO + ro + qtB[db]), pb[j], dvacc[db]);
-            dkacc[db] = mfma32(tr_pair(ldsQ + ro + qtA[db], ldsQ + ro + qtB[db]), dsb[j], dkacc[db]);
+            for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dpacc[v] = 0.f; }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                sacc = mfma32(uf.row(ldsK, kc), uf.row(ldsQ, kc), sacc);
+                dpacc = mfma32(uf.row(ldsV, kc), uf.row(ldsDO, kc), dpacc);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the phases apart (register pressure)
+            // ---- score function; keys past the end of the example's keys and queries past the end of the
+            // wave's queries (their rows repeat the last valid one) get zero weight
+            const bool q_ok = r < nq;
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int v = 8 * c + e;
+                    const float s = sacc[v] * sc;
+                    float pval, dsval;
+                    if (SOFTMAX) {
+                        pval = fast_exp2(s - lse2);
+                        dsval = pval * (dpacc[v] - delta) * p.scale;
+                    } else {
+                        float der;
+                        act_fast_vd<ACT>(s, pval, der);
+                        dsval = dpacc[v] * der * p.scale;
+                    }
+                    const bool ok = q_ok && n_kv > 4 * g && (unsigned)(8 * (v >> 2) + (v & 3)) < keys_left;
+                    pf[c][e] = (bf16_t)(ok ? pval : 0.f);
+                    dsf[c][e] = (bf16_t)(ok ? dsval : 0.f);
+                }
+        }
+        __syncthreads();  // every wave is done with the V tile: the P / dS tiles take its place
+        if (wave_active) {
+            // ---- dV^T += dO^T P, then dK^T += Q^T dS, over the wave's 32 queries.  P (then dS, in the same 2 KB)
+            // goes through LDS to come back as B operand (column = key, contraction over 16 queries per step);
+            // registers 4*vg .. 4*vg+3 of the C layout hold keys 8*vg + 4g + 0..3 of query r.
+#pragma unroll
+            for (int which = 0; which < 2; ++which) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const bf16x8 src = which == 0 ? pf[vg >> 1] : dsf[vg >> 1];
+                    const bf16x4 four = (vg & 1) ? __builtin_shufflevector(src, src, 4, 5, 6, 7) : __builtin_shufflevector(src, src, 0, 1, 2, 3);
+                    *(bf16x4*)(ldsP + pq_offset(r, (8 * vg + 4 * g) * 2)) = four;
+                }
+                bf16x8 back[2];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) back[j] = tr_pair(ldsP + j * 16 * 64 + ptA, ldsP + j * 16 * 64 + ptB);
+                const char* src_tile = which == 0 ? ldsDO : ldsQ;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int ro = j * 16 * L::ROW_BYTES;
+                        const bf16x8 a = tr_pair(src_tile + ro + qtA[db], src_tile + ro + qtB[db]);
+                        if (which == 0) dvacc[db] = mfma32(a, back[j], dvacc[db]);
+                        else dkacc[db] = mfma32(a, back[j], dkacc[db]);
+                    }
+            }
+            // ---- dQ^T = K^T dS^T, rows out through the wave's own Q / dO tiles: only this wave reads them,
+            // and the LDS operations of a wave complete in order
+            // (one 32-channel block at a time: 16 accumulator registers instead of 64)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                f32x16 dqacc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dqacc[v] = 0.f;
+#pragma unroll
+                for (int c = 0; c < 2; ++c) dqacc = mfma32(uf.transposed(ldsK, db, c), dsf[c], dqacc);
+                store_block_staged<D>(ldsQ, dqacc, db, lane);
+            }
+            store_staged_rows<D>(ldsQ, (bf16_t*)p.dq + rows0 * hd + (int64_t)h * D, hd, nq, lane);
         }
     }
     // ---- the four waves' contributions are added in LDS, dV first, then dK.  A wave's partial sums go
-    // into its own Q / dO tiles, which only that wave has read.
+    // into its own Q / dO tiles.
     char* mine = ldsQ;
     const int n_chunks = KT * D / 4;  // 16-byte chunks of a [32][D] fp32 tile
 #pragma unroll
@@ -789,15 +813,15 @@ __device__ __forceinline__ void bwd_fewkeys_item(const AttnParams& p, const floa
             for (int w = 0; w < 4; ++w) sum += *(const f32x4*)(lds + SM::HEAD + w * SM::WAVE + part_offset<D>(row, ch));
             *(f32x4*)(dst + row * D + ch * 4) = sum;
         }
-        __syncthreads();  // the partial tiles are rewritten: for dK, then as dQ staging rows
+        if (which == 0) __syncthreads();  // the partial tiles are rewritten for dK
     }
-    if (nq > 0) store_tile_rows<D>(mine, dqacc, (bf16_t*)p.dq + (q_row0 + q_lo_w) * hd + (int64_t)h * D, hd, nq, lane);
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void bwd_fewkeys_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
+__global__ __launch_bounds__(256, 2) void bwd_fewkeys_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                           const int32_t* __restrict__ tile_example,
-                                                          const float* __restrict__ delta_ws, float* __restrict__ partial) {
+                                                          const float* __restrict__ delta_ws, float* __restrict__ partial,
+                                                          int chunk_rows) {
     extern __shared__ __attribute__((aligned(1024))) char fk_lds[];
     int b, h, qt;
     if (!locate_tile(tile_start, tile_example, p.B, p.H, 1, b, h, qt)) return;
@@ -806,8 +830,8 @@ __global__ __launch_bounds__(256) void bwd_fewkeys_kernel(AttnParams p, const in
     n_kv = n_kv > KT ? KT : n_kv;  // the launch condition (max_kv <= 32) promises this; never read past the tile
     const int64_t q0 = q_begin(p, b);
     const int nq_all = (int)(q_end(p, b) - q0);
-    const int q_first = qt * TILE_ROWS;
-    const int nq = (nq_all - q_first) < TILE_ROWS ? (nq_all - q_first) : TILE_ROWS;
+    const int q_first = qt * chunk_rows;  // the tile table counts chunks of chunk_rows queries here
+    const int nq = (nq_all - q_first) < chunk_rows ? (nq_all - q_first) : chunk_rows;
     float* part_out = partial + ((size_t)(tile_start[b] + qt) * p.H + h) * (2 * KT * D);
     KUNLUN_ACT_SWITCH(p.head_act[h], (bwd_fewkeys_item<D, A>(p, delta_ws, fk_lds, h, q0 + q_first, nq, k0, n_kv, part_out)));
 }
@@ -859,13 +883,13 @@ static hipError_t launch_tiled(const AttnParams& p, char* ws, bool any_softmax, 
     }
     if (p.total_q > 0) {
         hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, q_tiles,
-                           tile_example_of(q_tiles, p.B));
+                           tile_example_of(q_tiles, p.B), TILE_ROWS);
         hipLaunchKernelGGL((bwd_dq_kernel<D, NW, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_q, runs)), dim3(64 * NW), 0,
                            stream, p, q_tiles, tile_example_of(q_tiles, p.B), runs, delta);
     }
     if (p.total_kv > 0) {
         hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.kv_off, 0, p.B, k_tiles,
-                           tile_example_of(k_tiles, p.B));
+                           tile_example_of(k_tiles, p.B), TILE_ROWS);
         hipLaunchKernelGGL((bwd_dkdv_kernel<D, NW, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_kv, runs)), dim3(64 * NW), 0,
                            stream, p, k_tiles, tile_example_of(k_tiles, p.B), runs, delta);
     }
@@ -889,11 +913,14 @@ static hipError_t launch_fewkeys(const AttnParams& p, char* ws, bool any_softmax
         hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            (const bf16_t*)p.o, (const bf16_t*)p.d_o, delta, p.total_q, p.H);
     }
+    const int chunk_rows = TILE_ROWS * fewkeys_chunk_tiles(p.B, p.H, p.total_q);
     hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, q_tiles,
-                       tile_example_of(q_tiles, p.B));
-    if (p.total_q > 0)
-        hipLaunchKernelGGL((bwd_fewkeys_kernel<D>), dim3(tile_grid(p.B, p.H, p.total_q, 1)), dim3(256), bytes, stream, p, q_tiles,
-                           tile_example_of(q_tiles, p.B), delta, partial);
+                       tile_example_of(q_tiles, p.B), chunk_rows);
+    if (p.total_q > 0) {
+        const int64_t per_xcd = ((p.total_q / chunk_rows + p.B) * p.H + 7) / 8;  // an upper bound of the chunk count sizes the grid
+        hipLaunchKernelGGL((bwd_fewkeys_kernel<D>), dim3((unsigned)((per_xcd + 1) * 8)), dim3(256), bytes, stream, p, q_tiles,
+                           tile_example_of(q_tiles, p.B), delta, partial, chunk_rows);
+    }
     if (p.total_kv > 0) {
         const int64_t threads = (int64_t)p.B * p.H * 2 * KT * (D / 4);
         hipLaunchKernelGGL((fewkeys_reduce_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, p, q_tiles,

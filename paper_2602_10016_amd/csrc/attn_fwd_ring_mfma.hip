@@ -263,7 +263,7 @@ static hipError_t launch_qtiled(const AttnParams& p, hipStream_t stream) {
     int32_t* tile_start = const_cast<int32_t*>(p.order);
     int32_t* tile_example = tile_example_of(tile_start, p.B);
     hipLaunchKernelGGL(tile_prefix_kernel<0>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, tile_start,
-                       tile_example);
+                       tile_example, TILE_ROWS);
     hipLaunchKernelGGL((qtile_fwd_mfma_kernel<D, NW, OCC, WINDOWED>), dim3(tile_grid(p.B, p.H, p.total_q, runs)),
                        dim3(64 * NW), 0, stream, p, tile_start, tile_example, runs);
     return hipGetLastError();

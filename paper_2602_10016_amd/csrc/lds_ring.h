@@ -100,8 +100,12 @@ struct TileDma {
     __device__ __forceinline__ void issue(const char* tile_base, int rows_left, uint32_t lds_tile) const {
         if (!active()) return;
         const int rows = rows_left < KT ? rows_left : KT;
-        const u32x4 rsrc = make_rsrc_words(tile_base, (uint32_t)(rows - 1) * row_bytes + ROW);
-        const uint32_t dst = lds_tile + wave_ * IPW * 1024;
+        // the descriptor and the LDS address are wave-uniform by construction; say so where the compiler
+        // cannot prove it (they are scalar operands of the load)
+        u32x4 rsrc = make_rsrc_words(tile_base, (uint32_t)(rows - 1) * row_bytes + ROW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rsrc[i] = __builtin_amdgcn_readfirstlane(rsrc[i]);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_tile + wave_ * IPW * 1024);
         if (rows == KT) {
 #pragma unroll
             for (int i = 0; i < IPW; ++i) load_to_lds_b128(rsrc, voff[i], 0, dst + i * 1024);

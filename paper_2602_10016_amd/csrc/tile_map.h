@@ -58,18 +58,19 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ tile_sta
     return true;
 }
 
-// Exclusive prefix sum of ceil(len_b / TILE_ROWS) over the examples, and the example of every
+// Exclusive prefix sum of ceil(len_b / tile_rows) over the examples, and the example of every
 // tile; single workgroup of 1024 threads.  off == null: every example has `dense_len` rows.
+// tile_rows is TILE_ROWS or a multiple of it (a workgroup that walks several tiles).
 // (A template only so that every translation unit that launches it carries its own copy.)
 template <int UNUSED>
 __global__ __launch_bounds__(1024) void tile_prefix_kernel(const int32_t* __restrict__ off, int dense_len, int B,
                                                            int32_t* __restrict__ tile_start,
-                                                           int32_t* __restrict__ tile_example) {
+                                                           int32_t* __restrict__ tile_example, int tile_rows) {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
     const int per = (B + 1023) / 1024;
     const int b0 = tid * per, b1 = (b0 + per < B) ? b0 + per : B;
-    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + TILE_ROWS - 1) / TILE_ROWS; };
+    auto tiles_of = [&](int b) { return ((off ? off[b + 1] - off[b] : dense_len) + tile_rows - 1) / tile_rows; };
     int sum = 0;
     for (int b = b0; b < b1; ++b) sum += tiles_of(b);
     part[tid] = sum;
