@@ -19,6 +19,8 @@
 // both as row fragments and transposed sits in LDS once, in the two-way swizzle.
 // Softmax heads use the forward LSE and delta = rowsum(dO * O), computed once by a small
 // kernel into the workspace; pass B streams both per query tile next to Q and dO.
+// Long query sequences over at most 32 keys per example (the PFFN direction proper) take a third
+// kernel at the end of this file that does everything in one pass over Q and dO.
 #include "lds_ring.h"
 #include "tile_map.h"
 
