@@ -560,6 +560,51 @@ def test_sumkron_backward_repeatable_and_empty_batch(kb):
     assert e[0].numel() == 0 and float(e[1].float().abs().max()) == 0.0 and float(e[2].float().abs().max()) == 0.0
 
 
+# ---------------- autograd wrappers ----------------
+
+def test_autograd_wrappers_route_to_the_library(kb):
+    """The torch.autograd.Function wrappers return exactly what the forward / backward entry points return."""
+    from paper_2602_10016_amd import autograd as ka
+    wl = W.make("cfg5", 9, B=12, lengths=("uniform", 8, 96), scale=0.125)
+    q, k, v, d_o = [to_dev(a, "bf16") for a in (wl.q, wl.k, wl.v, wl.d_o)]
+    kvo = offsets_dev(wl.kv_offsets)
+    acts = [0, 3, 5, 0][:wl.H] if wl.H <= 4 else None
+    for t in (q, k, v):
+        t.requires_grad_(True)
+    o = ka.gdpa(q, k, v, kvo, wl.scale, 3, max_q=wl.Nq, max_kv=wl.max_kv, head_act=acts)
+    o.backward(d_o)
+    o_ref, lse = kb.gdpa_fwd(q.detach(), k.detach(), v.detach(), kvo, wl.scale, 3, max_q=wl.Nq, max_kv=wl.max_kv, head_act=acts)
+    g_ref = kb.gdpa_bwd(q.detach(), k.detach(), v.detach(), d_o, kvo, wl.scale, 3, o=o_ref, lse=lse, max_q=wl.Nq,
+                        max_kv=wl.max_kv, head_act=acts)
+    torch.cuda.synchronize()
+    assert torch.equal(o.detach(), o_ref)
+    for t, g in zip((q, k, v), g_ref):
+        assert torch.equal(t.grad, g)
+
+    ws = W.make("cfg3", 9, B=4)
+    q, k, v = [to_dev(a, "bf16").requires_grad_(True) for a in (ws.q, ws.k, ws.v)]
+    off = offsets_dev(ws.kv_offsets)
+    d_o = to_dev(W.round_to_bf16(np.random.default_rng(3).standard_normal(ws.q.shape, dtype=np.float32)), "bf16")
+    o = ka.sliding_window_attention(q, k, v, off, 255, 0, ws.scale, max_len=ws.max_kv)
+    o.backward(d_o)
+    o_ref, lse = kb.swa_fwd(q.detach(), k.detach(), v.detach(), off, 255, 0, ws.scale, max_len=ws.max_kv)
+    g_ref = kb.swa_bwd(q.detach(), k.detach(), v.detach(), o_ref, lse, d_o, off, 255, 0, ws.scale, max_len=ws.max_kv)
+    torch.cuda.synchronize()
+    assert torch.equal(o.detach(), o_ref)
+    for t, g in zip((q, k, v), g_ref):
+        assert torch.equal(t.grad, g)
+
+    x, z, w = [to_dev(a, "bf16").requires_grad_(True) for a in _sumkron_inputs(90, 4, 128, 32, 128, 2, "bf16")]
+    dy = to_dev(_sumkron_dy(91, 4, 32, 128, "bf16"), "bf16")
+    y = ka.sumkron_linear(x, z, w)
+    y.backward(dy)
+    g_ref = kb.sumkron_bwd(x.detach(), z.detach(), w.detach(), dy)
+    torch.cuda.synchronize()
+    assert torch.equal(y.detach(), kb.sumkron_fwd(x.detach(), z.detach(), w.detach()))
+    for t, g in zip((x, z, w), g_ref):
+        assert torch.equal(t.grad, g)
+
+
 # ---------------- HIP graph capture ----------------
 
 def test_graph_capture_replays_match_eager(kb):
