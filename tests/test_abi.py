@@ -145,3 +145,14 @@ def test_sumkron_bwd_argument_validation_without_gpu(kb):
     # plain path: U and G in fp32
     assert kb.sumkron_bwd_workspace_bytes(3, 40, 6, 24, 3, kb.FP32) >= 2 * 3 * 6 * 3 * 24 * 4
     assert kb.sumkron_bwd_workspace_bytes(0, 256, 32, 384, 8) > 0     # an empty batch is a legal size
+
+
+def test_backward_workspace_covers_the_partial_sums_of_the_few_keys_path(kb):
+    B, H, d, T = 128, 4, 128, 150000
+    two_pass = kb.workspace_bytes(kb.OP_GDPA_BWD, B, H, d, 2048, 33, T, B * 33)
+    one_pass = kb.workspace_bytes(kb.OP_GDPA_BWD, B, H, d, 2048, 32, T, B * 32)
+    # (T/128 + B) * H = 5200 tile-heads: chunks of 4 tiles, one fp32 [2][32][d] partial tile per chunk and head
+    assert one_pass - two_pass >= (T // 512) * H * 2 * 32 * d * 4
+    # at most 64 queries per example: the fused kernel, no partial sums; the window op never takes this path
+    assert kb.workspace_bytes(kb.OP_GDPA_BWD, B, H, d, 64, 32, B * 64, B * 32) < (1 << 20)
+    assert kb.workspace_bytes(kb.OP_SWA_BWD, B, H, d, 32, 32, B * 32, B * 32) < (1 << 20)

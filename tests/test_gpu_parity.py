@@ -355,7 +355,11 @@ def test_cfg4_full_size_sliding_window_sampled(kb, oracle):
 
 # ---------------- config 5: backward ----------------
 
-def check_gdpa_bwd(kb, oracle, wl, act, head_act=None):
+def check_gdpa_bwd(kb, oracle, wl, act, head_act=None, long_sums=False):
+    """long_sums: dK and dV are sums over thousands of queries with scores of order one; the bf16 rounding of
+    P / dS then adds up to an error that scales with the typical output, not with the output at hand (a CPU
+    emulation of that rounding reproduces the GPU result to one output ulp), so those two use the criterion
+    for long sums, with the RMS taken per example and head (the sums of an example run over its own queries)."""
     dt = wl.dtype
     q, k, v, d_o = to_dev(wl.q, dt), to_dev(wl.k, dt), to_dev(wl.v, dt), to_dev(wl.d_o, dt)
     kvo, qo = offsets_dev(wl.kv_offsets), offsets_dev(wl.q_offsets)
@@ -369,8 +373,12 @@ def check_gdpa_bwd(kb, oracle, wl, act, head_act=None):
                                              q_offsets=wl.q_offsets, max_q=wl.Nq, head_act=head_act)
     tol = TOL[dt]
     assert_close(to_np(dq), dq_ref, tol, f"{wl.name} dQ act={act}")
-    assert_close(to_np(dk), dk_ref, tol, f"{wl.name} dK act={act}")
-    assert_close(to_np(dv), dv_ref, tol, f"{wl.name} dV act={act}")
+    if long_sums:
+        assert_close_sums(to_np(dk), dk_ref, tol, f"{wl.name} dK act={act}", offsets=wl.kv_offsets)
+        assert_close_sums(to_np(dv), dv_ref, tol, f"{wl.name} dV act={act}", offsets=wl.kv_offsets)
+    else:
+        assert_close(to_np(dk), dk_ref, tol, f"{wl.name} dK act={act}")
+        assert_close(to_np(dv), dv_ref, tol, f"{wl.name} dV act={act}")
 
 
 @pytest.mark.parametrize("act", ["gelu", "softmax"])
@@ -430,6 +438,29 @@ def test_backward_long_jagged_queries_at_most_32_keys(kb, oracle, d, act):
     check_gdpa_bwd(kb, oracle, wl, ACTS[act])
     if act == "gelu":
         check_gdpa_bwd(kb, oracle, wl, 0, head_act=[0, 5, 3])
+
+
+@pytest.mark.parametrize("d,B,lo,hi,chunk", [(128, 24, 1500, 2500, 2), (64, 48, 1000, 2000, 4), (32, 48, 4000, 8000, 8)])
+def test_backward_at_most_32_keys_chunked_workgroups(kb, oracle, d, B, lo, hi, chunk):
+    """Enough query tiles that a workgroup of the one-pass backward walks `chunk` tiles (the chunk length
+    grows with the tile count), with ragged ends, an example without queries and one with a single query."""
+    rng = np.random.default_rng(50 + d)
+    H = 8
+    lens_q = rng.integers(lo, hi + 1, size=B)
+    lens_q[3], lens_q[5] = 0, 1
+    lens_kv = rng.integers(1, 33, size=B)
+    lens_kv[0], lens_kv[1] = 32, 0
+    tiles = int(sum((n + 127) // 128 for n in lens_q))
+    total_q = int(lens_q.sum())
+    tile_heads = (total_q // 128 + B) * H   # the library's own measure
+    assert {8: tile_heads >= 16384, 4: 4096 <= tile_heads < 16384, 2: 2048 <= tile_heads < 4096}[chunk], (tiles, tile_heads)
+    wl = W.make("cfg5", 52, B=B, H=H, d=d, Nq=1, lengths=("list", lens_kv), scale=0.5 / math.sqrt(d))
+    q_off = W.offsets_from_lengths(lens_q)
+    wl.q = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32) * 0.5)
+    wl.d_o = W.round_to_bf16(rng.standard_normal((q_off[-1], H, d), dtype=np.float32))
+    wl.q_offsets, wl.Nq = q_off, None
+    wl.meta["max_q"] = int(lens_q.max())
+    check_gdpa_bwd(kb, oracle, wl, 0, head_act=[3, 0, 5, 2, 1, 4, 3, 0], long_sums=True)
 
 
 def test_backward_dense_long_queries_per_head(kb, oracle):
