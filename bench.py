@@ -36,7 +36,7 @@ ORACLE_SAMPLE_EXAMPLES = 256
 # profiles/bench_cfg4_hbm_traffic.txt.  Valid for the default workload and seed only.  (The
 # counters sit between L2 and the memory fabric: re-reads that the 256 MB Infinity Cache serves
 # are included, which is what the sliding-window figure above its algorithmic 9.38 GB shows.)
-MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957142000, "gdpa_bwd": 9780318000, "swa_fwd": 10265125000}
+MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957138000, "gdpa_bwd": 9780301000, "swa_fwd": 10268127000}
 
 
 def device_normal(torch, shape, sigma, seed):
