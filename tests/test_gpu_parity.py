@@ -677,6 +677,53 @@ def test_graph_capture_replays_match_eager(kb):
         del junk
 
 
+def test_graph_capture_of_the_later_entry_points(kb):
+    """The same for the sliding-window backward, the long-query backward with few keys (one-pass kernel with
+    partial sums in the workspace) and SumKronLinear forward / backward (split-K partial sums in the workspace)."""
+    rng = np.random.default_rng(77)
+    dt = "bf16"
+    ws3 = W.make("cfg3", 23, B=5)
+    qs, ks, vs, so = to_dev(ws3.q, dt), to_dev(ws3.k, dt), to_dev(ws3.v, dt), offsets_dev(ws3.kv_offsets)
+    dos = to_dev(W.round_to_bf16(rng.standard_normal(ws3.q.shape, dtype=np.float32)), dt)
+    o_s, lse_s = kb.swa_fwd(qs, ks, vs, so, 255, 0, ws3.scale, max_len=ws3.max_kv)
+    lens_q, lens_kv = np.array([700, 130, 0, 64, 300]), np.array([32, 7, 16, 0, 20])
+    H, d = 4, 128
+    q_off, kv_off = W.offsets_from_lengths(lens_q), W.offsets_from_lengths(lens_kv)
+    bf = lambda shape, s: to_dev(W.round_to_bf16((rng.standard_normal(shape) * s).astype(np.float32)), dt)
+    q, d_o = bf((q_off[-1], H, d), 0.5), bf((q_off[-1], H, d), 1.0)
+    k, v = bf((kv_off[-1], H, d), 0.5), bf((kv_off[-1], H, d), 0.5)
+    qo, kvo = offsets_dev(q_off), offsets_dev(kv_off)
+    x, z, w = [to_dev(a, dt) for a in _sumkron_inputs(92, 8, 128, 32, 128, 2, dt)]
+    dy = to_dev(_sumkron_dy(93, 8, 32, 128, dt), dt)
+    w1 = torch.empty(kb.workspace_bytes(kb.OP_SWA_BWD, 5, ws3.H, ws3.d, ws3.max_kv, ws3.max_kv, qs.shape[0], qs.shape[0]), dtype=torch.uint8, device="cuda")
+    w2 = torch.empty(kb.workspace_bytes(kb.OP_GDPA_BWD, 5, H, d, 700, 32, q.shape[0], k.shape[0]), dtype=torch.uint8, device="cuda")
+    w3 = torch.empty(kb.sumkron_workspace_bytes(8, 128, 32, 128, 2), dtype=torch.uint8, device="cuda")
+    w4 = torch.empty(kb.sumkron_bwd_workspace_bytes(8, 128, 32, 128, 2), dtype=torch.uint8, device="cuda")
+
+    def run():
+        a = kb.swa_bwd(qs, ks, vs, o_s, lse_s, dos, so, 255, 0, ws3.scale, max_len=ws3.max_kv, workspace=w1)
+        b = kb.gdpa_bwd(q, k, v, d_o, kvo, 0.04, 3, q_offsets=qo, max_q=700, max_kv=32, workspace=w2)
+        y = kb.sumkron_fwd(x, z, w, workspace=w3)
+        c = kb.sumkron_bwd(x, z, w, dy, workspace=w4)
+        return list(a) + list(b) + [y] + list(c)
+
+    eager = [t.clone() for t in run()]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = run()
+    for rep in range(3):
+        for t in captured:
+            t.zero_()
+        junk = torch.randn(1 << 20, device="cuda").sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (got, ref) in enumerate(zip(captured, eager)):
+            assert torch.equal(got, ref), f"replay {rep}: output {i} differs from the eager result"
+        del junk
+
+
 # ---------------- degenerate calls ----------------
 
 def test_empty_batch_and_all_empty_histories(kb):
