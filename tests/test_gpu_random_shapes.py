@@ -66,8 +66,10 @@ def test_gdpa_forward_backward_random_shapes(kb, oracle, seed):
             assert_lse_close(to_np(lse)[h], lse_ref[h], 1e-2, what + f" lse h={h}")
     dq_ref, dk_ref, dv_ref = oracle.gdpa_bwd(c["q"], c["k"], c["v"], c["d_o"], c["kv_off"], c["scale"], 0, **kw)
     assert_close(to_np(dq), dq_ref, TOL["bf16"], what + " dQ")
-    assert_close(to_np(dk), dk_ref, TOL["bf16"], what + " dK")
-    assert_close(to_np(dv), dv_ref, TOL["bf16"], what + " dV")
+    # dK / dV sum over up to 300 queries whose weights were rounded to bf16 (softmax over one or two keys:
+    # weights of order one): error relative to the typical output of the same example and head
+    assert_close_sums(to_np(dk), dk_ref, TOL["bf16"], what + " dK", offsets=c["kv_off"])
+    assert_close_sums(to_np(dv), dv_ref, TOL["bf16"], what + " dV", offsets=c["kv_off"])
 
 
 @pytest.mark.parametrize("seed", range(max(1, 2 * N_CASES // 3)))
