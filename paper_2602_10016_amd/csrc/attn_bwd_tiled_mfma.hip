@@ -17,8 +17,9 @@
 // and the streamed operand is read transposed from LDS (ds_read_b64_tr_b16).  Streamed tiles
 // travel by buffer-load-to-LDS into a ring of three stages (lds_ring.h); a tile that is read
 // both as row fragments and transposed sits in LDS once, in the two-way swizzle.
-// Softmax heads use the forward LSE and delta = rowsum(dO * O), computed once by a small
-// kernel into the workspace; pass B streams both per query tile next to Q and dO.
+// Softmax heads use the forward LSE and delta = rowsum(dO * O); pass A computes delta of its query
+// tile from the O rows and leaves it in the workspace, pass B streams LSE and delta per query tile next
+// to Q and dO.
 // Long query sequences over at most 32 keys per example (the PFFN direction proper) take a third
 // kernel at the end of this file that does everything in one pass over Q and dO.
 #include "lds_ring.h"
@@ -128,7 +129,7 @@ struct UFrag {
 // ------------------------------------------------------------------ pass A: dQ
 
 template <int D, int NW, int ACT, bool WINDOWED>
-__device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __restrict__ delta_ws, char* lds, int h,
+__device__ __forceinline__ void bwd_dq_item(const AttnParams& p, float* __restrict__ delta_ws, char* lds, int h,
                                             int64_t q_row0, int nq_wg, int64_t t0_wg, int64_t k0, int n_kv) {
     using PT = PadTiles<D>;
     using L = TileLayout<D>;
@@ -197,15 +198,29 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, const float* __
         for (int kc = 0; kc < KC; ++kc) dof[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
         __syncthreads();
     }
-    if (n_steps > 1) issue(kt_begin + 1, 1);
-
-    // this lane's query: softmax statistics and visible key range
+    // this lane's query: softmax statistics.  delta = rowsum(dO * O) is computed here from the O rows of the
+    // tile (the dO fragments are at hand; each lane half covers half of the channels) and stored for pass B.
     float lse2 = INFINITY, delta = 0.f;
-    if (SOFTMAX && r < nq) {
-        const int64_t idx = (int64_t)h * p.total_q + q_row0 + q_lo_w + r;
-        lse2 = p.lse[idx] * LOG2E_T;
-        delta = delta_ws[idx];
+    if (SOFTMAX) {
+        char* own = lds + SM::TOTAL - SM::OWN_BYTES;
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.o + q_row0 * hd + (int64_t)h * D), row_bytes, nq_wg, tid);
+        __syncthreads();
+        float part = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 of = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part = fmaf((float)of[e], (float)dof[kc][e], part);
+        }
+        delta = halves_sum(part);
+        if (r < nq) {
+            const int64_t idx = (int64_t)h * p.total_q + q_row0 + q_lo_w + r;
+            lse2 = p.lse[idx] * LOG2E_T;
+            if (g == 0) delta_ws[idx] = delta;
+        }
+        __syncthreads();
     }
+    if (n_steps > 1) issue(kt_begin + 1, 1);
     int key_lo;
     unsigned key_span;
     {
@@ -511,7 +526,7 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
 template <int D, int NW, bool WINDOWED>
 __global__ __launch_bounds__(64 * NW, D == 128 ? 2 : 3) void bwd_dq_kernel(AttnParams p, const int32_t* __restrict__ tile_start,
                                                             const int32_t* __restrict__ tile_example, int runs,
-                                                            const float* __restrict__ delta_ws) {
+                                                            float* __restrict__ delta_ws) {
     __shared__ __attribute__((aligned(1024))) char lds[TiledSmem<D, 0>::TOTAL];
     static_assert(32 * NW == TILE_ROWS, "tile size of the work mapping");
     int b, h, qt;
@@ -878,11 +893,7 @@ static hipError_t launch_tiled(const AttnParams& p, char* ws, bool any_softmax, 
     int32_t* k_tiles = (int32_t*)(ws + tile_table_bytes(p.B, p.total_q));
     float* delta = (float*)(ws + tile_table_bytes(p.B, p.total_q) + tile_table_bytes(p.B, p.total_kv));
     const int runs = tile_runs(WINDOWED, p.left, p.right, p.H);
-    if (any_softmax && p.total_q > 0) {
-        const int64_t threads = p.total_q * p.H * (D / 8);
-        hipLaunchKernelGGL((delta_kernel<D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                           (const bf16_t*)p.o, (const bf16_t*)p.d_o, delta, p.total_q, p.H);
-    }
+    (void)any_softmax;  // pass A computes delta of its softmax heads itself and leaves it in the workspace for pass B
     if (p.total_q > 0) {
         hipLaunchKernelGGL(tile_prefix_kernel<1>, dim3(1), dim3(1024), 0, stream, p.q_off, p.max_q, p.B, q_tiles,
                            tile_example_of(q_tiles, p.B), TILE_ROWS);
