@@ -36,7 +36,11 @@ struct FwdSmem {
     static constexpr int K_TILE = KT * K_STRIDE;
     static constexpr int V_TILE = KT * V_STRIDE;
     static constexpr int BUF_BYTES = K_TILE + V_TILE;  // K tile, then V tile
-    static constexpr int TOTAL = 2 * BUF_BYTES;        // double buffer
+    static constexpr int TOTAL = 2 * BUF_BYTES;        // double buffer (workgroups of several waves)
+    // A wave that streams alone needs no second buffer (it writes a tile, reads it, and writes the next one in
+    // program order); the key-split launches use that to fit four waves' buffers, the others keep two buffers
+    // (the store of the next tile can then be scheduled before the reads of the current one end).
+    static constexpr int bytes(int ks) { return ks > 1 ? BUF_BYTES : TOTAL; }
 };
 
 // Cooperative global -> register -> LDS staging of one 32-row tile by a workgroup of 64*NW
@@ -88,16 +92,25 @@ struct CoopTile {
 };
 
 // One work item.  q_row0 / nq_wg: first query row (global) and query count of the workgroup's tile.
-template <int D, int NQB, int NW, int ACT>
+// KS > 1 (with NW = 1): the workgroup has KS waves that own the SAME queries and take the key tiles of the
+// item in turn (wave s: tiles s, s + KS, ...), each with its own tile buffers and no barrier in the key loop;
+// their partial results are merged in LDS at the end, in wave order.  For launches with few work items, where
+// one wave per item would leave the time to the longest history.
+template <int D, int NQB, int NW, int ACT, int AHEAD, int KS>
 __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, int h, int64_t q_row0, int nq_wg,
                                               int64_t k0, int n_kv) {
     using SM = FwdSmem<D>;
     using CT = CoopTile<D, NW>;
+    static_assert(KS == 1 || NW == 1, "key splitting is for single-wave query groups");
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16;  // contraction steps of S^T = K Q^T
     constexpr int DB = D / 32;  // 32-channel blocks of O^T
     constexpr int QW = 32 * NQB;  // queries per wave
-    const int tid = threadIdx.x;
+    const int split = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6) : 0;  // this wave's turn in the key tiles
+    const int tid = KS > 1 ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
+    constexpr int LDS_BYTES = SM::bytes(KS);  // of one query-owning group of waves
+    char* const lds_all = lds;
+    lds += split * LDS_BYTES;
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
@@ -113,6 +126,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     nq = nq < 0 ? 0 : (nq > QW ? QW : nq);
     const bool wave_active = nq > 0;
     const int kt_end = (n_kv + KT - 1) / KT;  // key tiles of the item
+    const int n_local = kt_end > split ? (kt_end - split + KS - 1) / KS : 0;  // ... of this wave: split + i*KS
 
     CT ct;
     ct.init(tid, row_bytes);
@@ -130,7 +144,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     // read as zero), staged in LDS in the K-tile row layout, and each wave picks its fragments.
     constexpr int QT = QW * NW;
     constexpr int Q_LOADS = QT * CT::CHUNKS / (64 * NW);
-    static_assert(QT * SM::K_STRIDE <= SM::TOTAL, "query tile must fit the tile buffers");
+    static_assert(QT * SM::K_STRIDE <= LDS_BYTES, "query tile must fit the tile buffers");
     bf16x8 qf[NQB][KC];
     {
         const char* qbase = (const char*)(Q + q_row0 * hd + (int64_t)h * D);
@@ -167,20 +181,22 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     for (int qb = 0; qb < NQB; ++qb) { m_ref[qb] = -INFINITY; l_run[qb] = 0.f; }
     const float sc = SOFTMAX ? p.scale * LOG2E : p.scale;
 
-    // Tiles ahead of the one being consumed are in flight in registers: two (sets A and B,
-    // used alternately) for streamed keys when the per-thread share is small enough, else one.
-    constexpr bool PF2 = CT::LOADS <= 4;
-    constexpr int AHEAD = PF2 ? 2 : 1;
-    u32x4 kstA[CT::LOADS], vstA[CT::LOADS], kstB[CT::LOADS], vstB[CT::LOADS];
-    auto fetch = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt) {
+    // AHEAD tiles ahead of the one being consumed are in flight in registers (AHEAD register sets,
+    // used in turn): one tile costs a full memory round trip, so a wave that walks its history alone
+    // moves AHEAD tiles per round trip.
+    static_assert(AHEAD == 1 || AHEAD % 2 == 0, "the LDS double buffer alternates with the tile index");
+    u32x4 kst[AHEAD][CT::LOADS], vst[AHEAD][CT::LOADS];
+    auto fetch = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int i) {
+        const int kt = split + i * KS;
         if (kt < kt_end) {
             const int rows = n_kv - kt * KT;
             ct.template load<true>(ks, K + kt * tile_bytes, rows);
             ct.template load<true>(vs, V + kt * tile_bytes, rows);
         }
     };
-    auto compute = [&](const char* ldsK, const char* ldsV, int kt) {
+    auto compute = [&](const char* ldsK, const char* ldsV, int i) {
         if (!wave_active) return;
+        const int kt = split + i * KS;
         // ---- S^T = K Q^T
         f32x16 sacc[NQB];
 #pragma unroll
@@ -216,22 +232,87 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
             }
         }
     };
-    auto step = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int kt, int buf) {
-        char* ldsK = lds + buf * SM::BUF_BYTES;
+    auto step = [&](u32x4 (&ks)[CT::LOADS], u32x4 (&vs)[CT::LOADS], int i, int buf) {
+        char* ldsK = lds + (KS > 1 ? 0 : buf) * SM::BUF_BYTES;
         char* ldsV = ldsK + SM::K_TILE;
         ct.store(ldsK, ldsV, ks, vs);
-        // tile kt is complete in LDS; every wave is also done with the other buffer (tile kt-1)
+        // the tile is complete in LDS; every wave is also done with the other buffer (the tile before)
         if (NW > 1) __syncthreads();
-        fetch(ks, vs, kt + AHEAD);
-        compute(ldsK, ldsV, kt);
+        fetch(ks, vs, i + AHEAD);
+        compute(ldsK, ldsV, i);
     };
-    fetch(kstA, vstA, 0);
-    if (PF2) fetch(kstB, vstB, 1);
-    for (int kt = 0; kt < kt_end; kt += 2) {
-        step(kstA, vstA, kt, 0);
-        if (kt + 1 < kt_end) {
-            if (PF2) step(kstB, vstB, kt + 1, 1);
-            else step(kstA, vstA, kt + 1, 1);
+#pragma unroll
+    for (int j = 0; j < AHEAD; ++j) fetch(kst[j], vst[j], j);
+    if (AHEAD == 1) {
+        for (int i = 0; i < n_local; i += 2) {
+            step(kst[0], vst[0], i, 0);
+            if (i + 1 < n_local) step(kst[0], vst[0], i + 1, 1);
+        }
+    } else {
+        for (int i = 0; i < n_local; i += AHEAD) {
+#pragma unroll
+            for (int j = 0; j < AHEAD; ++j)
+                if (i + j < n_local) step(kst[j], vst[j], i + j, j & 1);
+        }
+    }
+
+    if (KS > 1) {
+        // ---- merge of the KS partial results (wave 0 collects, in wave order): every other wave leaves its
+        // accumulators, lane by lane, in its own idle tile buffers, with the softmax reference and sum
+        constexpr int STAT = DB * NQB * 4 * 1024;  // byte offset of the statistics behind the accumulators
+        static_assert(STAT + NQB * 2 * 256 <= LDS_BYTES, "partial results must fit the tile buffers");
+        if (split > 0) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+                    for (int vg = 0; vg < 4; ++vg) {
+                        f32x4 x;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) x[e] = oacc[db][qb][4 * vg + e];
+                        *(f32x4*)(lds + ((db * NQB + qb) * 4 + vg) * 1024 + lane * 16) = x;
+                    }
+            if (SOFTMAX) {
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb) {
+                    *(float*)(lds + STAT + (2 * qb) * 256 + lane * 4) = m_ref[qb];
+                    *(float*)(lds + STAT + (2 * qb + 1) * 256 + lane * 4) = l_run[qb];
+                }
+            }
+        }
+        __syncthreads();
+        if (split > 0) return;
+        for (int w = 1; w < KS; ++w) {
+            const char* part = lds_all + w * LDS_BYTES;
+            float cw[NQB];
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+                cw[qb] = 1.f;
+                if (SOFTMAX) {
+                    const float mw = *(const float*)(part + STAT + (2 * qb) * 256 + lane * 4);
+                    const float lw = *(const float*)(part + STAT + (2 * qb + 1) * 256 + lane * 4);
+                    const float m_new = fmaxf(m_ref[qb], mw);
+                    const float c0 = m_ref[qb] == -INFINITY ? 0.f : fast_exp2(m_ref[qb] - m_new);
+                    cw[qb] = mw == -INFINITY ? 0.f : fast_exp2(mw - m_new);
+                    l_run[qb] = l_run[qb] * c0 + lw * cw[qb];
+                    m_ref[qb] = m_new;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) oacc[db][qb][v] *= c0;
+                }
+            }
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+                    for (int vg = 0; vg < 4; ++vg) {
+                        const f32x4 x = *(const f32x4*)(part + ((db * NQB + qb) * 4 + vg) * 1024 + lane * 16);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) oacc[db][qb][4 * vg + e] = fmaf(x[e], cw[qb], oacc[db][qb][4 * vg + e]);
+                    }
         }
     }
 
@@ -275,24 +356,24 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     }
 }
 
-template <int D, int NQB, int NW>
+template <int D, int NQB, int NW, int AHEAD, int KS>
 __device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds, int act, int h, int64_t q_row0,
                                                   int nq, int64_t k0, int n_kv) {
     switch (act) {
-    case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_IDENTITY>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_SOFTMAX: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SOFTMAX, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_IDENTITY: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_IDENTITY, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
     }
 }
 
 // GDPA / cross attention: one workgroup per (example, query tile, head), examples in scheduler
 // order (longest history first).
-template <int D, int NQB, int NW, int OCC>
-__global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
-    __shared__ __attribute__((aligned(1024))) char lds[FwdSmem<D>::TOTAL];
+template <int D, int NQB, int NW, int OCC, int AHEAD, int KS>
+__global__ __launch_bounds__(64 * NW * KS, OCC) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];  // KS * FwdSmem<D>::bytes(KS) bytes
     constexpr int QT = 32 * NQB * NW;
     // Workgroup i runs on XCD i % 8.  Consecutive entries (example, query tile) go to
     // consecutive XCDs and each XCD walks through all heads of its entries, so that every L2
@@ -313,7 +394,7 @@ __global__ __launch_bounds__(64 * NW, OCC) void gdpa_fwd_mfma_kernel(AttnParams 
     const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
     const int64_t k0 = p.kv_off[b];
     const int n_kv = p.kv_off[b + 1] - (int)k0;
-    attn_fwd_dispatch<D, NQB, NW>(p, lds, p.head_act[h], h, qb0 + q_first, nq, k0, n_kv);
+    attn_fwd_dispatch<D, NQB, NW, AHEAD, KS>(p, lds, p.head_act[h], h, qb0 + q_first, nq, k0, n_kv);
 }
 
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
@@ -325,12 +406,19 @@ bool mfma_fwd_supported(const AttnParams& p, int dtype) {
     return true;
 }
 
-template <int D, int NQB, int NW, int OCC>
+template <int D, int NQB, int NW, int OCC, int AHEAD, int KS = 1>
 static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
     constexpr int QT = 32 * NQB * NW;
+    constexpr int bytes = KS * FwdSmem<D>::bytes(KS);
+    auto kern = gdpa_fwd_mfma_kernel<D, NQB, NW, OCC, AHEAD, KS>;
+    if (bytes > 64 * 1024) {
+        // once per process (thread-safe initialisation of a function-local static); not a stream operation
+        static const hipError_t raised = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (raised != hipSuccess) return raised;
+    }
     const int n_qtiles = (p.max_q + QT - 1) / QT;
     const unsigned grid = (unsigned)((((int64_t)p.B * n_qtiles + 7) / 8) * 8 * p.H);
-    hipLaunchKernelGGL((gdpa_fwd_mfma_kernel<D, NQB, NW, OCC>), dim3(grid), dim3(64 * NW), 0, stream, p, n_qtiles);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW * KS), bytes, stream, p, n_qtiles);
     return hipGetLastError();
 }
 
@@ -340,11 +428,18 @@ hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream) {
     // 32 queries per wave, up to 255 registers per wave, two or three waves per SIMD.
     // Query-tiled launches use 128-query tiles (4 waves): fewer K/V tile loads per query.
     if (mfma_fwd_is_qtiled(p)) return launch_mfma_fwd_qtiled(p, stream);
-    if (p.max_q <= 32)
-        return p.d == 128 ? launch_gdpa<128, 1, 1, 2>(p, stream)
-               : p.d == 64 ? launch_gdpa<64, 1, 1, 2>(p, stream) : launch_gdpa<32, 1, 1, 2>(p, stream);
-    return p.d == 128 ? launch_gdpa<128, 1, 2, 2>(p, stream)
-           : p.d == 64 ? launch_gdpa<64, 1, 2, 2>(p, stream) : launch_gdpa<32, 1, 2, 2>(p, stream);
+    // Up to 32 queries per example = one wave per (example, head).  With few work items (every wave has a SIMD to
+    // itself) the longest history and the score function of a single wave would set the time: four waves (two at
+    // d = 128) then share the key tiles of an item.  (cfg2, GELU: 48 -> 40 us cold; the floor of that launch -
+    // identity scores - is 37 us for its 156 MB.)
+    const bool few_items = (int64_t)p.B * p.H <= 2048;
+    if (p.max_q <= 32) {
+        if (p.d == 128) return few_items ? launch_gdpa<128, 1, 1, 2, 1, 2>(p, stream) : launch_gdpa<128, 1, 1, 2, 1>(p, stream);
+        if (p.d == 64) return few_items ? launch_gdpa<64, 1, 1, 2, 2, 4>(p, stream) : launch_gdpa<64, 1, 1, 2, 2>(p, stream);
+        return few_items ? launch_gdpa<32, 1, 1, 2, 2, 4>(p, stream) : launch_gdpa<32, 1, 1, 2, 2>(p, stream);
+    }
+    return p.d == 128 ? launch_gdpa<128, 1, 2, 2, 2>(p, stream)
+           : p.d == 64 ? launch_gdpa<64, 1, 2, 2, 2>(p, stream) : launch_gdpa<32, 1, 2, 2, 2>(p, stream);
 }
 
 }  // namespace kunlun
