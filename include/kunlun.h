@@ -97,8 +97,9 @@ typedef enum { KUNLUN_OP_GDPA_FWD = 0, KUNLUN_OP_GDPA_BWD = 1, KUNLUN_OP_SWA_FWD
  *   lse          out, device, float [H, total_q], may be NULL; written for softmax heads only
  *   q_offsets    in,  device int32 [B+1] or NULL (dense queries: max_q rows per example)
  *   kv_offsets   in,  device int32 [B+1]
- *   max_q,max_kv upper bounds on the per-example query / key counts (sizing only; the true
- *                counts come from the offsets); total_q, total_kv: row counts of q and k
+ *   max_q,max_kv upper bounds on the per-example query / key counts: they size work lists and
+ *                select kernels, the true counts come from the offsets and must not exceed them
+ *                (results are undefined if they do); total_q, total_kv: row counts of q and k
  *   scale        multiplies the dot products (1/tau for GDPA, 1/sqrt(d) for softmax)
  *   act          kunlun_act used by every head unless head_act is given
  *   head_act     in, HOST int32 [H] or NULL: per-head kunlun_act ("Act_h")
