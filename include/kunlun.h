@@ -192,6 +192,15 @@ int kunlun_sumkron_bwd(const void* x, const void* z, const void* w, const void* 
 /* Bytes of workspace that kunlun_sumkron_bwd needs for these sizes (0 for invalid sizes). */
 size_t kunlun_sumkron_bwd_workspace_bytes(int B, int S, int T, int D, int k, int dtype);
 
+/*
+ * Debug aid for the jagged layout ("Offsets are trusted" above: the operators do not check them).  Enqueues
+ * one small kernel that counts the violations of the contract - offsets[0] != 0, offsets[B] != total, an
+ * example shorter than 0 or longer than max_len - into *violations (out, device, one int32; 0 = the array is
+ * fine).  offsets: in, device int32 [B+1].  Asynchronous like every other call: read *violations after the
+ * stream has been synchronised.  Errors as for the other entry points.
+ */
+int kunlun_check_offsets(const int32_t* offsets, int B, int64_t total, int max_len, int32_t* violations, void* stream);
+
 /* Static, human-readable text for a kunlun_status. */
 const char* kunlun_strerror(int status);
 

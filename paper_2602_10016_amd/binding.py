@@ -23,7 +23,7 @@ ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
-           "kunlun_strerror"]
+           "kunlun_check_offsets", "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -47,6 +47,8 @@ _lib.kunlun_sumkron_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _
 _lib.kunlun_sumkron_bwd.restype = _i
 _lib.kunlun_sumkron_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
 _lib.kunlun_sumkron_bwd_workspace_bytes.restype = _sz
+_lib.kunlun_check_offsets.argtypes = [_vp, _i, _i64, _i, _vp, _vp]
+_lib.kunlun_check_offsets.restype = _i
 _lib.kunlun_strerror.argtypes = [_i]
 _lib.kunlun_strerror.restype = ctypes.c_char_p
 
@@ -207,3 +209,13 @@ def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
     if rc != OK:
         raise KunlunError(rc)
     return dx, dz, dw
+
+
+
+def check_offsets(offsets, total, max_len, *, stream=None) -> int:
+    """kunlun_check_offsets, then a synchronising read of the count (0 = the offsets obey the contract)."""
+    out = torch.empty(1, dtype=torch.int32, device=offsets.device)
+    rc = _lib.kunlun_check_offsets(_ptr(offsets), offsets.numel() - 1, int(total), int(max_len), _ptr(out), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return int(out.item())

@@ -104,6 +104,14 @@ int kunlun_sumkron_bwd(const void* x, const void* z, const void* w, const void* 
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 
+int kunlun_check_offsets(const int32_t* offsets, int B, int64_t total, int max_len, int32_t* violations, void* stream) {
+    if (B < 0 || total < 0 || max_len < 0) return KUNLUN_ERR_SHAPE;
+    if (!offsets || !violations) return KUNLUN_ERR_NULL;
+    if (!aligned(offsets, 4) || !aligned(violations, 4)) return KUNLUN_ERR_ALIGN;
+    const hipError_t e = launch_check_offsets(offsets, B, total, max_len, violations, (hipStream_t)stream);
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
 const char* kunlun_strerror(int status) {
     switch (status) {
     case KUNLUN_OK: return "ok";

@@ -36,6 +36,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
+hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int max_len, int32_t* violations, hipStream_t stream);
 // True when the launch is so small that every workgroup is resident at once (wgs_per_cu = how
 // many workgroups of the kernel fit one compute unit): the issue order then has no effect and
 // the sorting kernel is skipped.

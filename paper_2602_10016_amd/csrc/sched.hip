@@ -53,6 +53,32 @@ __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(const int32_t* 
     }
 }
 
+// Debug aid: counts the ways in which an offsets array breaks the contract (offsets[0] = 0, lengths in
+// [0, max_len], offsets[B] = total); one workgroup, deterministic.
+__global__ __launch_bounds__(SCHED_THREADS) void check_offsets_kernel(const int32_t* __restrict__ off, int B, int64_t total,
+                                                                       int max_len, int32_t* __restrict__ violations) {
+    __shared__ int bad[SCHED_THREADS];
+    const int tid = threadIdx.x;
+    int n = 0;
+    for (int b = tid; b < B; b += SCHED_THREADS) {
+        const int64_t len = (int64_t)off[b + 1] - off[b];
+        n += (len < 0 || len > max_len) ? 1 : 0;
+    }
+    if (tid == 0) n += (off[0] != 0 ? 1 : 0) + ((int64_t)off[B] != total ? 1 : 0);
+    bad[tid] = n;
+    __syncthreads();
+    for (int s = SCHED_THREADS / 2; s > 0; s >>= 1) {
+        if (tid < s) bad[tid] += bad[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) *violations = bad[0];
+}
+
+hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int max_len, int32_t* violations, hipStream_t stream) {
+    hipLaunchKernelGGL(check_offsets_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, off, B, total, max_len, violations);
+    return hipGetLastError();
+}
+
 // MI355X has 256 compute units.
 bool schedule_is_moot(int64_t workgroups, int wgs_per_cu) { return workgroups <= (int64_t)wgs_per_cu * 256; }
 

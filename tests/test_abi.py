@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 10
+    assert len(declared) == 11
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
@@ -156,3 +156,11 @@ def test_backward_workspace_covers_the_partial_sums_of_the_few_keys_path(kb):
     # at most 64 queries per example: the fused kernel, no partial sums; the window op never takes this path
     assert kb.workspace_bytes(kb.OP_GDPA_BWD, B, H, d, 64, 32, B * 64, B * 32) < (1 << 20)
     assert kb.workspace_bytes(kb.OP_SWA_BWD, B, H, d, 32, 32, B * 32, B * 32) < (1 << 20)
+
+
+def test_check_offsets_argument_validation_without_gpu(kb):
+    lib = kb.raw()
+    call = lambda off=0x1000, B=4, total=100, max_len=64, out=0x1000: lib.kunlun_check_offsets(off, B, total, max_len, out, None)
+    assert call(B=-1) == kb.ERR_SHAPE and call(total=-1) == kb.ERR_SHAPE and call(max_len=-1) == kb.ERR_SHAPE
+    assert call(off=None) == kb.ERR_NULL and call(out=None) == kb.ERR_NULL
+    assert call(off=0x1002) == kb.ERR_ALIGN and call(out=0x1001) == kb.ERR_ALIGN

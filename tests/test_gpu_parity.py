@@ -724,6 +724,17 @@ def test_graph_capture_of_the_later_entry_points(kb):
         del junk
 
 
+def test_check_offsets_counts_contract_violations(kb):
+    good = np.array([0, 5, 5, 40, 100], dtype=np.int32)
+    assert kb.check_offsets(offsets_dev(good), 100, 64) == 0
+    assert kb.check_offsets(offsets_dev(good), 100, 50) == 1          # one example longer than max_len
+    assert kb.check_offsets(offsets_dev(good), 99, 64) == 1           # last offset is not the total
+    bad = np.array([1, 5, 3, 40, 100], dtype=np.int32)                # first offset not 0, one negative length
+    assert kb.check_offsets(offsets_dev(bad), 100, 64) == 2
+    big = W.offsets_from_lengths(np.full(5000, 7))
+    assert kb.check_offsets(offsets_dev(big), 35000, 7) == 0          # more examples than threads
+
+
 # ---------------- degenerate calls ----------------
 
 def test_empty_batch_and_all_empty_histories(kb):
