@@ -211,7 +211,6 @@ def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
     return dx, dz, dw
 
 
-
 def check_offsets(offsets, total, max_len, *, stream=None) -> int:
     """kunlun_check_offsets, then a synchronising read of the count (0 = the offsets obey the contract)."""
     out = torch.empty(1, dtype=torch.int32, device=offsets.device)
