@@ -76,6 +76,59 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _check(name, t, *, dtype=None, shape=None, like=None, optional=False):
+    """The C ABI sees plain pointers and trusts the layout, so a wrong dtype (int64 offsets read as int32), a
+    strided view or a host tensor would be read as something else without any error.  Reject them here:
+    TypeError for a wrong type or dtype, ValueError for a wrong layout, shape or device."""
+    if t is None:
+        if optional:
+            return
+        raise TypeError(f"{name}: a tensor is required")
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch.Tensor, got {type(t).__name__}")
+    want = like.dtype if (dtype is None and like is not None) else dtype
+    if want is not None and t.dtype != want:
+        raise TypeError(f"{name}: dtype {t.dtype}, expected {want}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous (got strides {tuple(t.stride())} for shape {tuple(t.shape)})")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+
+
+def _on_device(**tensors):
+    """Last check of every entry point (after types, layouts and shapes): all tensors on one HIP device."""
+    dev = None
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if not t.is_cuda:
+            raise ValueError(f"{name}: must be a CUDA (HIP) tensor, got device {t.device}")
+        if dev is None:
+            dev = t.device
+        elif t.device != dev:
+            raise ValueError(f"{name}: on {t.device}, expected {dev}")
+
+
+def _check_qkv(q, k, v):
+    if not isinstance(q, torch.Tensor) or q.dim() != 3:
+        raise ValueError("q: expected a [rows, H, d] tensor")
+    _dtype_code(q)
+    _check("q", q)
+    H, d = q.shape[1], q.shape[2]
+    if not isinstance(k, torch.Tensor) or k.dim() != 3:
+        raise ValueError("k: expected a [rows, H, d] tensor")
+    _check("k", k, like=q, shape=(k.shape[0], H, d))
+    _check("v", v, like=q, shape=tuple(k.shape))
+
+
+def _check_offsets(name, off, B=None, optional=False):
+    if off is None and optional:
+        return
+    _check(name, off, dtype=torch.int32)
+    if off.dim() != 1 or off.numel() < 1 or (B is not None and off.numel() != B + 1):
+        raise ValueError(f"{name}: expected int32 [B+1]" + (f" with B = {B}" if B is not None else "") + f", got shape {tuple(off.shape)}")
+
+
 def _dtype_code(t):
     if t.dtype == torch.bfloat16:
         return BF16
@@ -89,34 +142,41 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _head_act(head_act):
+def _head_act(head_act, H):
     if head_act is None:
         return None
+    if len(head_act) != H:
+        raise ValueError(f"head_act: {len(head_act)} entries, expected one per head ({H})")
     return (ctypes.c_int32 * len(head_act))(*[int(a) for a in head_act])
 
 
 def _workspace(workspace, nbytes, device):
     if workspace is None:
-        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    _check("workspace", workspace, dtype=torch.uint8)
     return workspace
 
 
 def gdpa_fwd(q, k, v, kv_offsets, scale, act, *, q_offsets=None, max_q=None, max_kv, head_act=None, out=None,
              lse=None, want_lse=True, workspace=None, stream=None):
     """kunlun_gdpa_fwd.  q [total_q,H,d], k/v [total_kv,H,d] device tensors; returns (o, lse)."""
+    _check_qkv(q, k, v)
     total_q, H, d = q.shape
     total_kv = k.shape[0]
+    _check_offsets("kv_offsets", kv_offsets)
     B = kv_offsets.numel() - 1
-    if q_offsets is None:
-        assert max_q is not None
-    elif max_q is None:
-        raise ValueError("max_q is required with q_offsets")
+    _check_offsets("q_offsets", q_offsets, B, optional=True)
+    if max_q is None:
+        raise ValueError("max_q is required (queries per example, or their upper bound with q_offsets)")
     o = torch.empty_like(q) if out is None else out
+    _check("out", o, like=q, shape=tuple(q.shape))
     if lse is None and want_lse:
         lse = torch.empty((H, total_q), dtype=torch.float32, device=q.device)
+    _check("lse", lse, dtype=torch.float32, like=None, shape=(H, total_q), optional=True)
     nbytes = workspace_bytes(OP_GDPA_FWD, B, H, d, max_q, max_kv, total_q, total_kv)
+    ha = _head_act(head_act, H)
     ws = _workspace(workspace, nbytes, q.device)
-    ha = _head_act(head_act)
+    _on_device(q=q, k=k, v=v, kv_offsets=kv_offsets, q_offsets=q_offsets, out=o, lse=lse, workspace=ws)
     rc = _lib.kunlun_gdpa_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(q_offsets), _ptr(kv_offsets), B, H,
                               d, int(max_q), int(max_kv), total_q, total_kv, float(scale), int(act), ha,
                               _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
@@ -125,16 +185,37 @@ def gdpa_fwd(q, k, v, kv_offsets, scale, act, *, q_offsets=None, max_q=None, max
     return o, lse
 
 
+def _grads(out, q, k, v):
+    if out is None:
+        return torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dq, dk, dv = out
+    _check("out[0] (dq)", dq, like=q, shape=tuple(q.shape))
+    _check("out[1] (dk)", dk, like=q, shape=tuple(k.shape))
+    _check("out[2] (dv)", dv, like=q, shape=tuple(v.shape))
+    return dq, dk, dv
+
+
 def gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, *, o=None, lse=None, q_offsets=None, max_q=None, max_kv,
-             head_act=None, workspace=None, stream=None):
-    """kunlun_gdpa_bwd.  Returns (dq, dk, dv).  o and lse are the forward results (softmax heads)."""
+             head_act=None, out=None, workspace=None, stream=None):
+    """kunlun_gdpa_bwd.  Returns (dq, dk, dv) (written into the tensors of `out` when given).  o and lse are
+    the forward results (read for softmax heads)."""
+    _check_qkv(q, k, v)
     total_q, H, d = q.shape
     total_kv = k.shape[0]
+    _check("d_o", d_o, like=q, shape=tuple(q.shape))
+    _check("o", o, like=q, shape=tuple(q.shape), optional=True)
+    _check("lse", lse, dtype=torch.float32, shape=(H, total_q), optional=True)
+    _check_offsets("kv_offsets", kv_offsets)
     B = kv_offsets.numel() - 1
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    _check_offsets("q_offsets", q_offsets, B, optional=True)
+    if max_q is None:
+        raise ValueError("max_q is required (queries per example, or their upper bound with q_offsets)")
+    dq, dk, dv = _grads(out, q, k, v)
     nbytes = workspace_bytes(OP_GDPA_BWD, B, H, d, max_q, max_kv, total_q, total_kv)
+    ha = _head_act(head_act, H)
     ws = _workspace(workspace, nbytes, q.device)
-    ha = _head_act(head_act)
+    _on_device(q=q, k=k, v=v, d_o=d_o, o=o, lse=lse, kv_offsets=kv_offsets, q_offsets=q_offsets, dq=dq, dk=dk, dv=dv,
+               workspace=ws)
     rc = _lib.kunlun_gdpa_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
                               _ptr(q_offsets), _ptr(kv_offsets), B, H, d, int(max_q), int(max_kv), total_q, total_kv,
                               float(scale), int(act), ha, _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
@@ -146,13 +227,20 @@ def gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, *, o=None, lse=None, q_offset
 def swa_fwd(q, k, v, offsets, window_left, window_right, scale, *, max_len, out=None, lse=None, want_lse=True,
             workspace=None, stream=None):
     """kunlun_swa_fwd.  q, k, v [total,H,d] share `offsets`; returns (o, lse)."""
+    _check_qkv(q, k, v)
     total, H, d = q.shape
+    if k.shape[0] != total:
+        raise ValueError(f"k: {k.shape[0]} rows, expected {total} (self-attention: q, k, v share the offsets)")
+    _check_offsets("offsets", offsets)
     B = offsets.numel() - 1
     o = torch.empty_like(q) if out is None else out
+    _check("out", o, like=q, shape=tuple(q.shape))
     if lse is None and want_lse:
         lse = torch.empty((H, total), dtype=torch.float32, device=q.device)
+    _check("lse", lse, dtype=torch.float32, shape=(H, total), optional=True)
     nbytes = workspace_bytes(OP_SWA_FWD, B, H, d, max_len, max_len, total, total)
     ws = _workspace(workspace, nbytes, q.device)
+    _on_device(q=q, k=k, v=v, offsets=offsets, out=o, lse=lse, workspace=ws)
     rc = _lib.kunlun_swa_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(offsets), B, H, d, int(max_len),
                              total, int(window_left), int(window_right), float(scale), _dtype_code(q), _ptr(ws),
                              ws.numel(), _stream(stream))
@@ -161,14 +249,23 @@ def swa_fwd(q, k, v, offsets, window_left, window_right, scale, *, max_len, out=
     return o, lse
 
 
-def swa_bwd(q, k, v, o, lse, d_o, offsets, window_left, window_right, scale, *, max_len, workspace=None,
+def swa_bwd(q, k, v, o, lse, d_o, offsets, window_left, window_right, scale, *, max_len, out=None, workspace=None,
             stream=None):
-    """kunlun_swa_bwd.  o and lse are the results of swa_fwd.  Returns (dq, dk, dv)."""
+    """kunlun_swa_bwd.  o and lse are the results of swa_fwd.  Returns (dq, dk, dv) (written into the tensors
+    of `out` when given)."""
+    _check_qkv(q, k, v)
     total, H, d = q.shape
+    if k.shape[0] != total:
+        raise ValueError(f"k: {k.shape[0]} rows, expected {total} (self-attention: q, k, v share the offsets)")
+    _check("o", o, like=q, shape=tuple(q.shape))
+    _check("d_o", d_o, like=q, shape=tuple(q.shape))
+    _check("lse", lse, dtype=torch.float32, shape=(H, total))
+    _check_offsets("offsets", offsets)
     B = offsets.numel() - 1
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    dq, dk, dv = _grads(out, q, k, v)
     nbytes = workspace_bytes(OP_SWA_BWD, B, H, d, max_len, max_len, total, total)
     ws = _workspace(workspace, nbytes, q.device)
+    _on_device(q=q, k=k, v=v, o=o, lse=lse, d_o=d_o, offsets=offsets, dq=dq, dk=dk, dv=dv, workspace=ws)
     rc = _lib.kunlun_swa_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
                              _ptr(offsets), B, H, d, int(max_len), total, int(window_left), int(window_right),
                              float(scale), _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
@@ -183,10 +280,18 @@ def sumkron_workspace_bytes(B, S, T, D, k, dtype=BF16) -> int:
 
 def sumkron_fwd(x, z, w, *, out=None, workspace=None, stream=None):
     """kunlun_sumkron_fwd.  x [B,S,D], z [k,S,T], w [k,D,D] device tensors; returns y [B,T,D]."""
+    _dtype_code(x)
+    _check("x", x)
+    if x.dim() != 3 or z.dim() != 3:
+        raise ValueError("x: expected [B, S, D]; z: expected [k, S, T]")
     B, S, D = x.shape
     k, _, T = z.shape
+    _check("z", z, like=x, shape=(k, S, T))
+    _check("w", w, like=x, shape=(k, D, D))
     y = torch.empty((B, T, D), dtype=x.dtype, device=x.device) if out is None else out
+    _check("out", y, like=x, shape=(B, T, D))
     ws = _workspace(workspace, sumkron_workspace_bytes(B, S, T, D, k, _dtype_code(x)), x.device)
+    _on_device(x=x, z=z, w=w, out=y, workspace=ws)
     rc = _lib.kunlun_sumkron_fwd(_ptr(x), _ptr(z), _ptr(w), _ptr(y), B, S, T, D, k, _dtype_code(x), _ptr(ws), ws.numel(),
                                  _stream(stream))
     if rc != OK:
@@ -200,10 +305,18 @@ def sumkron_bwd_workspace_bytes(B, S, T, D, k, dtype=BF16) -> int:
 
 def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
     """kunlun_sumkron_bwd.  x [B,S,D], z [k,S,T], w [k,D,D], dy [B,T,D] device tensors; returns (dx, dz, dw)."""
+    _dtype_code(x)
+    _check("x", x)
+    if x.dim() != 3 or z.dim() != 3:
+        raise ValueError("x: expected [B, S, D]; z: expected [k, S, T]")
     B, S, D = x.shape
     k, _, T = z.shape
+    _check("z", z, like=x, shape=(k, S, T))
+    _check("w", w, like=x, shape=(k, D, D))
+    _check("dy", dy, like=x, shape=(B, T, D))
     dx, dz, dw = torch.empty_like(x), torch.empty_like(z), torch.empty_like(w)
     ws = _workspace(workspace, sumkron_bwd_workspace_bytes(B, S, T, D, k, _dtype_code(x)), x.device)
+    _on_device(x=x, z=z, w=w, dy=dy, workspace=ws)
     rc = _lib.kunlun_sumkron_bwd(_ptr(x), _ptr(z), _ptr(w), _ptr(dy), _ptr(dx), _ptr(dz), _ptr(dw), B, S, T, D, k,
                                  _dtype_code(x), _ptr(ws), ws.numel(), _stream(stream))
     if rc != OK:
@@ -213,6 +326,8 @@ def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
 
 def check_offsets(offsets, total, max_len, *, stream=None) -> int:
     """kunlun_check_offsets, then a synchronising read of the count (0 = the offsets obey the contract)."""
+    _check_offsets("offsets", offsets)
+    _on_device(offsets=offsets)
     out = torch.empty(1, dtype=torch.int32, device=offsets.device)
     rc = _lib.kunlun_check_offsets(_ptr(offsets), offsets.numel() - 1, int(total), int(max_len), _ptr(out), _stream(stream))
     if rc != OK:

@@ -246,8 +246,10 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
     p.B = B; p.H = H; p.d = d; p.max_q = max_len; p.max_kv = max_len;
     p.total_q = total; p.total_kv = total; p.scale = scale;
     p.windowed = 1;
-    p.left = window_left < 0 ? -1 : window_left;
-    p.right = window_right < 0 ? -1 : window_right;
+    // a reach of max_len or more covers every sequence: treated as unbounded, which also keeps the kernels'
+    // 32-bit window arithmetic (position + reach) far from overflow
+    p.left = (window_left < 0 || window_left >= max_len) ? -1 : window_left;
+    p.right = (window_right < 0 || window_right >= max_len) ? -1 : window_right;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (mfma_fwd_supported(p, dtype)) {
@@ -283,8 +285,10 @@ int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, c
     p.B = B; p.H = H; p.d = d; p.max_q = max_len; p.max_kv = max_len;
     p.total_q = total; p.total_kv = total; p.scale = scale;
     p.windowed = 1;
-    p.left = window_left < 0 ? -1 : window_left;
-    p.right = window_right < 0 ? -1 : window_right;
+    // a reach of max_len or more covers every sequence: treated as unbounded, which also keeps the kernels'
+    // 32-bit window arithmetic (position + reach) far from overflow
+    p.left = (window_left < 0 || window_left >= max_len) ? -1 : window_left;
+    p.right = (window_right < 0 || window_right >= max_len) ? -1 : window_right;
     hipError_t e;
     if (mfma_bwd_tiled_supported(p, dtype))
         e = launch_mfma_bwd_tiled(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), true, (hipStream_t)stream);

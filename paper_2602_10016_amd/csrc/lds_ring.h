@@ -25,18 +25,25 @@ __device__ __forceinline__ u32x4 make_rsrc_words(const void* base, uint32_t byte
 
 // One wave-wide load from a buffer straight into LDS: lane l's 16 (4) bytes land at
 // lds_addr + 16*l (4*l).  voff: per-lane byte offset, soff: uniform byte offset.  Counted by vmcnt.
+// The statements overwrite M0 (the LDS base of such a load) and say so in their clobber lists, so that the
+// compiler never assumes a value of its own survives in M0 across them.  M0 is a reserved register on this
+// target; the compiler's remark that it cannot save and restore a reserved register is what is meant here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds_b128(u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 __device__ __forceinline__ void load_to_lds_b32(u32x4 rsrc, uint32_t voff, uint32_t soff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
+
+#pragma clang diagnostic pop
 
 // s_waitcnt that waits only for the vector-memory counter to drop to N (other counters untouched).
 template <int N>

@@ -1,8 +1,10 @@
 // Generic (non matrix-core) kernels: fp32 storage and arithmetic, or any head dimension
 // the MFMA kernels do not tile.  One wavefront per output row; lanes run over keys for the
 // score dot products and over channels for the weighted sums.  Exact transcendental
-// functions.  These kernels serve the fp32 data type and small head dimensions; the bf16
-// hot path lives in gdpa_fwd_mfma.hip / swa_fwd_mfma.hip / gdpa_bwd_mfma.hip.
+// functions.  These kernels serve the fp32 data type and the head dimensions other than 32, 64
+// and 128; the bf16 hot path lives in attn_fwd_mfma.hip (streaming forward), attn_fwd_ring_mfma.hip
+// (query-tiled forward: sliding window, long query sequences), attn_bwd_pair_mfma.hip /
+// attn_bwd_mfma.hip (fused backward) and attn_bwd_tiled_mfma.hip (two-pass and few-keys backward).
 //
 // Forward: Eq. (GDPA) and softmax attention (Eq. (PMA), Eq. (seed-level attention),
 // Eq. (sliding window)).  Backward: gradients of <O, dO>, scores recomputed per row.

@@ -315,30 +315,31 @@ __global__ __launch_bounds__(256) void transpose_z_kernel(const bf16_t* __restri
     zt[idx] = z[((int64_t)i * S + s) * T + t];
 }
 
-// ---- plain kernels (fp32, or shapes the tiled kernel does not take): one thread per output element
+// ---- plain kernels (fp32, or shapes the tiled kernel does not take): one thread per output element; sums and the
+// intermediate U in fp64, so that the only rounding of an fp32 result is the final one
 template <typename T_>
 __global__ __launch_bounds__(256) void sumkron_stage1_plain(const T_* __restrict__ x, const T_* __restrict__ z,
-                                                            float* __restrict__ u, int B, int S, int T, int D, int k) {
+                                                            double* __restrict__ u, int B, int S, int T, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // ((b*T + t)*k + i)*D + c
     if (idx >= (int64_t)B * T * k * D) return;
     const int c = (int)(idx % D);
     const int i = (int)((idx / D) % k);
     const int t = (int)((idx / ((int64_t)D * k)) % T);
     const int64_t b = idx / ((int64_t)D * k * T);
-    float acc = 0.f;
-    for (int s = 0; s < S; ++s) acc = fmaf(to_float(z[((int64_t)i * S + s) * T + t]), to_float(x[(b * S + s) * D + c]), acc);
+    double acc = 0.0;
+    for (int s = 0; s < S; ++s) acc += (double)to_float(z[((int64_t)i * S + s) * T + t]) * (double)to_float(x[(b * S + s) * D + c]);
     u[idx] = acc;
 }
 template <typename T_>
-__global__ __launch_bounds__(256) void sumkron_stage2_plain(const float* __restrict__ u, const T_* __restrict__ w,
+__global__ __launch_bounds__(256) void sumkron_stage2_plain(const double* __restrict__ u, const T_* __restrict__ w,
                                                             T_* __restrict__ y, int64_t rows, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // row*D + e, row = b*T + t
     if (idx >= rows * D) return;
     const int e = (int)(idx % D);
     const int64_t row = idx / D;
-    float acc = 0.f;
-    for (int jc = 0; jc < k * D; ++jc) acc = fmaf(u[row * (int64_t)k * D + jc], to_float(w[(int64_t)jc * D + e]), acc);
-    y[idx] = from_float<T_>(acc);
+    double acc = 0.0;
+    for (int jc = 0; jc < k * D; ++jc) acc += u[row * (int64_t)k * D + jc] * (double)to_float(w[(int64_t)jc * D + e]);
+    y[idx] = from_float<T_>((float)acc);
 }
 
 bool sumkron_tiled_supported(int S, int T, int D, int k, int dtype) {
@@ -352,7 +353,7 @@ bool sumkron_bwd_tiled_supported(int B, int S, int T, int D, int k, int dtype) {
 size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype) {
     if (sumkron_tiled_supported(S, T, D, k, dtype))
         return align_up((size_t)k * T * S * 2, 256) + align_up((size_t)B * T * k * D * 2, 256);
-    return align_up((size_t)B * T * k * D * sizeof(float), 256);
+    return align_up((size_t)B * T * k * D * sizeof(double), 256);
 }
 
 static unsigned gemm_grid(int64_t units, int tiles_per_unit) { return (unsigned)(((units + 7) / 8) * 8 * tiles_per_unit); }
@@ -426,7 +427,7 @@ hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, 
         launch_gemm<false, false>(g2, stream);
         return hipGetLastError();
     }
-    float* u = (float*)workspace;
+    double* u = (double*)workspace;
     const int64_t n1 = (int64_t)B * T * k * D, n2 = (int64_t)B * T * D;
     if (dtype == KUNLUN_BF16) {
         hipLaunchKernelGGL(sumkron_stage1_plain<bf16_t>, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, stream,
@@ -465,57 +466,57 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(T_* __restrict__ p, int6
     if (idx < n) p[idx] = from_float<T_>(0.f);
 }
 
-// plain kernels: one thread per output element, fp32 (the two sums over the batch accumulate in fp64);
-// u and gq are [B*T][k][D] fp32
+// plain kernels: one thread per output element; every sum and the intermediates in fp64;
+// u and gq are [B*T][k][D] fp64
 template <typename T_>
-__global__ __launch_bounds__(256) void sumkron_g_plain(const T_* __restrict__ dy, const T_* __restrict__ w, float* __restrict__ gq,
+__global__ __launch_bounds__(256) void sumkron_g_plain(const T_* __restrict__ dy, const T_* __restrict__ w, double* __restrict__ gq,
                                                        int64_t rows, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (row*k + i)*D + c
     if (idx >= rows * k * D) return;
     const int c = (int)(idx % D);
     const int i = (int)((idx / D) % k);
     const int64_t row = idx / ((int64_t)D * k);
-    float acc = 0.f;
-    for (int e = 0; e < D; ++e) acc = fmaf(to_float(dy[row * D + e]), to_float(w[((int64_t)i * D + c) * D + e]), acc);
+    double acc = 0.0;
+    for (int e = 0; e < D; ++e) acc += (double)to_float(dy[row * D + e]) * (double)to_float(w[((int64_t)i * D + c) * D + e]);
     gq[idx] = acc;
 }
 template <typename T_>
-__global__ __launch_bounds__(256) void sumkron_dx_plain(const T_* __restrict__ z, const float* __restrict__ gq, T_* __restrict__ dx,
+__global__ __launch_bounds__(256) void sumkron_dx_plain(const T_* __restrict__ z, const double* __restrict__ gq, T_* __restrict__ dx,
                                                         int B, int S, int T, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (b*S + s)*D + c
     if (idx >= (int64_t)B * S * D) return;
     const int c = (int)(idx % D);
     const int s = (int)((idx / D) % S);
     const int64_t b = idx / ((int64_t)D * S);
-    float acc = 0.f;
+    double acc = 0.0;
     for (int i = 0; i < k; ++i)
         for (int t = 0; t < T; ++t)
-            acc = fmaf(to_float(z[((int64_t)i * S + s) * T + t]), gq[(((b * T + t) * k) + i) * D + c], acc);
-    dx[idx] = from_float<T_>(acc);
+            acc += (double)to_float(z[((int64_t)i * S + s) * T + t]) * gq[(((b * T + t) * k) + i) * D + c];
+    dx[idx] = from_float<T_>((float)acc);
 }
 template <typename T_>
-__global__ __launch_bounds__(256) void sumkron_dw_plain(const float* __restrict__ u, const T_* __restrict__ dy, T_* __restrict__ dw,
+__global__ __launch_bounds__(256) void sumkron_dw_plain(const double* __restrict__ u, const T_* __restrict__ dy, T_* __restrict__ dw,
                                                         int64_t rows, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (i*D + c)*D + e
     if (idx >= (int64_t)k * D * D) return;
     const int e = (int)(idx % D);
     const int c = (int)((idx / D) % D);
     const int i = (int)(idx / ((int64_t)D * D));
-    double acc = 0.0;  // a sum over the whole batch: fp64 keeps the fp32 result within its last bits
-    for (int64_t row = 0; row < rows; ++row) acc += (double)u[(row * k + i) * D + c] * (double)to_float(dy[row * D + e]);
+    double acc = 0.0;
+    for (int64_t row = 0; row < rows; ++row) acc += u[(row * k + i) * D + c] * (double)to_float(dy[row * D + e]);
     dw[idx] = from_float<T_>((float)acc);
 }
 template <typename T_>
-__global__ __launch_bounds__(256) void sumkron_dz_plain(const T_* __restrict__ x, const float* __restrict__ gq, T_* __restrict__ dz,
+__global__ __launch_bounds__(256) void sumkron_dz_plain(const T_* __restrict__ x, const double* __restrict__ gq, T_* __restrict__ dz,
                                                         int B, int S, int T, int D, int k) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // (i*S + s)*T + t
     if (idx >= (int64_t)k * S * T) return;
     const int t = (int)(idx % T);
     const int s = (int)((idx / T) % S);
     const int i = (int)(idx / ((int64_t)T * S));
-    double acc = 0.0;  // a sum over the whole batch, as above
+    double acc = 0.0;
     for (int64_t b = 0; b < B; ++b)
-        for (int c = 0; c < D; ++c) acc += (double)to_float(x[(b * S + s) * D + c]) * (double)gq[(((b * T + t) * k) + i) * D + c];
+        for (int c = 0; c < D; ++c) acc += (double)to_float(x[(b * S + s) * D + c]) * gq[(((b * T + t) * k) + i) * D + c];
     dz[idx] = from_float<T_>((float)acc);
 }
 
@@ -528,8 +529,8 @@ static BwdLayout sumkron_bwd_layout(int B, int S, int T, int D, int k, int dtype
     const size_t ukd = (size_t)B * T * k * D;
     if (!sumkron_bwd_tiled_supported(B, S, T, D, k, dtype)) {
         l.u = 0;
-        l.gq = align_up(ukd * sizeof(float), 256);
-        l.total = l.gq + align_up(ukd * sizeof(float), 256);
+        l.gq = align_up(ukd * sizeof(double), 256);
+        l.total = l.gq + align_up(ukd * sizeof(double), 256);
         return l;
     }
     l.zt = 0;
@@ -547,7 +548,7 @@ size_t sumkron_bwd_workspace(int B, int S, int T, int D, int k, int dtype) { ret
 
 template <typename T_>
 static void launch_bwd_plain(const T_* x, const T_* z, const T_* w, const T_* dy, T_* dx, T_* dz, T_* dw, int B, int S, int T,
-                             int D, int k, float* u, float* gq, hipStream_t stream) {
+                             int D, int k, double* u, double* gq, hipStream_t stream) {
     const int64_t rows = (int64_t)B * T, n1 = rows * k * D;
     auto blocks = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
     hipLaunchKernelGGL(sumkron_stage1_plain<T_>, blocks(n1), dim3(256), 0, stream, x, z, u, B, S, T, D, k);
@@ -576,10 +577,10 @@ hipError_t launch_sumkron_bwd(const void* x, const void* z, const void* w, const
     if (!sumkron_bwd_tiled_supported(B, S, T, D, k, dtype)) {
         if (dtype == KUNLUN_BF16)
             launch_bwd_plain<bf16_t>((const bf16_t*)x, (const bf16_t*)z, (const bf16_t*)w, (const bf16_t*)dy, (bf16_t*)dx,
-                                     (bf16_t*)dz, (bf16_t*)dw, B, S, T, D, k, (float*)(ws + l.u), (float*)(ws + l.gq), stream);
+                                     (bf16_t*)dz, (bf16_t*)dw, B, S, T, D, k, (double*)(ws + l.u), (double*)(ws + l.gq), stream);
         else
             launch_bwd_plain<float>((const float*)x, (const float*)z, (const float*)w, (const float*)dy, (float*)dx, (float*)dz,
-                                    (float*)dw, B, S, T, D, k, (float*)(ws + l.u), (float*)(ws + l.gq), stream);
+                                    (float*)dw, B, S, T, D, k, (double*)(ws + l.u), (double*)(ws + l.gq), stream);
         return hipGetLastError();
     }
     bf16_t* zt = (bf16_t*)(ws + l.zt);

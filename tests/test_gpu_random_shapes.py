@@ -117,7 +117,7 @@ def test_sumkron_forward_backward_random_shapes(kb, oracle, seed):
     x, z, w, dy = draw((B, S, D), 1.0), draw((k, S, T), 1 / math.sqrt(S)), draw((k, D, D), 1 / math.sqrt(D)), draw((B, T, D), 1.0)
     if dtype == "bf16":
         x, z, w, dy = [W.round_to_bf16(a) for a in (x, z, w, dy)]
-    tol = TOL["bf16"] if dtype == "bf16" else 2e-5
+    tol = TOL[dtype]
     what = f"seed {seed}: {dtype} B={B} S={S} T={T} D={D} k={k}"
     xd, zd, wd, dyd = [to_dev(a, dtype) for a in (x, z, w, dy)]
     y = kb.sumkron_fwd(xd, zd, wd)
@@ -126,6 +126,8 @@ def test_sumkron_forward_backward_random_shapes(kb, oracle, seed):
     assert_close(to_np(y), oracle.sumkron_fwd(x, z, w), tol, what + " Y")
     rx, rz, rw = oracle.sumkron_bwd(x, z, w, dy)
     assert_close(to_np(dx), rx, tol, what + " dX")
-    # sums over the batch of products with a rounded factor (bf16 or fp32 intermediates): error relative to the typical output
-    assert_close_sums(to_np(dz), rz, tol, what + " dZ")
-    assert_close_sums(to_np(dw), rw, tol, what + " dW")
+    # bf16: sums over the batch of products with a bf16-rounded factor - error relative to the typical output;
+    # fp32 (fp64 sums and intermediates inside the kernels): the standard criterion
+    sums = assert_close if dtype == "fp32" else assert_close_sums
+    sums(to_np(dz), rz, tol, what + " dZ")
+    sums(to_np(dw), rw, tol, what + " dW")
