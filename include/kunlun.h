@@ -111,6 +111,29 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
                     size_t workspace_bytes, void* stream);
 
 /*
+ * kunlun_gdpa_fwd for callers that cannot allocate device memory - code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc - and therefore cannot provide a workspace.  Same arguments, same kernels
+ * and bit-identical results, but no workspace: the work lists go into a fixed array of
+ * KUNLUN_STATIC_SCRATCH_BYTES of device memory that is part of the library image (each GPU the library runs on
+ * holds its own copy until the process ends).  The call allocates and frees nothing and enqueues kernels only (no
+ * memset: nothing in the array has to start at zero).
+ *   Limit: kunlun_workspace_bytes(KUNLUN_OP_GDPA_FWD, ...) of the call must not exceed
+ *   KUNLUN_STATIC_SCRATCH_BYTES (about 4 (2 B + total_q / 128) + 1 KiB: e.g. B = 100 000 examples of 64 queries);
+ *   larger calls return KUNLUN_ERR_WORKSPACE and enqueue nothing.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams,
+ *   or graphs that hold such calls replayed concurrently) race on it - order them, or use kunlun_gdpa_fwd with
+ *   separate workspaces.
+ *   The first call on a device looks the array's address up (hipGetSymbolAddress, once per device, under a
+ *   mutex): make that first call outside stream capture.  The device that is current at the call must be the
+ *   device of `stream` and of the tensors.
+ * Other errors as for kunlun_gdpa_fwd; the address lookup failing gives KUNLUN_ERR_LAUNCH.
+ */
+#define KUNLUN_STATIC_SCRATCH_BYTES (1 << 20)
+int kunlun_gdpa_fwd_static(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
+                           const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                           int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* stream);
+
+/*
  * Backward of kunlun_gdpa_fwd: dq, dk, dv (out, device, shaped like q, k, v, fully
  * overwritten) from q, k, v and the upstream gradient d_o (in, device, like q).
  * With p the weight of a (query, key) pair and dp = <dO_row, V_row>:

@@ -21,7 +21,7 @@ ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = -1,
 BF16, FP32 = 0, 1
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
-EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
+EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
            "kunlun_check_offsets", "kunlun_strerror"]
 
@@ -29,6 +29,9 @@ _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
                                  _vp, _sz, _vp]
 _lib.kunlun_gdpa_fwd.restype = _i
+_lib.kunlun_gdpa_fwd_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i, _vp]
+_lib.kunlun_gdpa_fwd_static.restype = _i
+STATIC_SCRATCH_BYTES = 1 << 20
 _lib.kunlun_gdpa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64,
                                  _i64, _f, _i, _vp, _i, _vp, _sz, _vp]
 _lib.kunlun_gdpa_bwd.restype = _i
@@ -183,6 +186,27 @@ def gdpa_fwd(q, k, v, kv_offsets, scale, act, *, q_offsets=None, max_q=None, max
     if rc != OK:
         raise KunlunError(rc)
     return o, lse
+
+
+def gdpa_fwd_static(q, k, v, kv_offsets, scale, act, *, out, lse=None, q_offsets=None, max_q, max_kv, head_act=None,
+                    stream=None):
+    """kunlun_gdpa_fwd_static: the forward call without a workspace and without any allocation - the caller
+    passes the outputs (out, and lse for softmax heads); returns (out, lse)."""
+    _check_qkv(q, k, v)
+    total_q, H, d = q.shape
+    _check_offsets("kv_offsets", kv_offsets)
+    B = kv_offsets.numel() - 1
+    _check_offsets("q_offsets", q_offsets, B, optional=True)
+    _check("out", out, like=q, shape=tuple(q.shape))
+    _check("lse", lse, dtype=torch.float32, shape=(H, total_q), optional=True)
+    ha = _head_act(head_act, H)
+    _on_device(q=q, k=k, v=v, kv_offsets=kv_offsets, q_offsets=q_offsets, out=out, lse=lse)
+    rc = _lib.kunlun_gdpa_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(q_offsets), _ptr(kv_offsets), B, H,
+                                     d, int(max_q), int(max_kv), total_q, k.shape[0], float(scale), int(act), ha,
+                                     _dtype_code(q), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return out, lse
 
 
 def _grads(out, q, k, v):

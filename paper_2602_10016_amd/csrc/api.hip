@@ -129,6 +129,18 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
                     const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
                     int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
                     size_t workspace_bytes, void* stream) {
+    return kunlun::gdpa_fwd_checked(q, k, v, o, lse, q_offsets, kv_offsets, B, H, d, max_q, max_kv, total_q, total_kv, scale, act,
+                                    head_act, dtype, workspace, workspace_bytes, stream, true);
+}
+
+}  // extern "C"
+
+// The forward entry point proper.  launch = false: validation only (every check of the entry point, nothing
+// enqueued, no device touched).
+int kunlun::gdpa_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
+                             const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
+                             int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
+                             size_t workspace_bytes, void* stream, bool launch) {
     int rc = check_common(B, H, d, max_q, max_kv, total_q, total_kv, scale, dtype);
     if (rc != KUNLUN_OK) return rc;
     AttnParams p;
@@ -146,6 +158,7 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
     if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_GDPA_FWD, B, H, d, max_q, max_kv, total_q, total_kv))
         return KUNLUN_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+    if (!launch) return KUNLUN_OK;
 
     p.q = q; p.k = k; p.v = v; p.o = o; p.lse = lse;
     p.q_off = q_offsets; p.kv_off = kv_offsets;
@@ -172,6 +185,8 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
     }
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
+
+extern "C" {
 
 int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
                     void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H,

@@ -34,6 +34,12 @@ struct AttnParams {
 constexpr size_t WS_HEADER_BYTES = 256;  // counters
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// kunlun_gdpa_fwd with one more argument: launch = false validates only (nothing enqueued, no device touched).
+int gdpa_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
+                     const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv,
+                     float scale, int act, const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes,
+                     void* stream, bool launch);
+
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
 hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int max_len, int32_t* violations, hipStream_t stream);

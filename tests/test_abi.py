@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 11
+    assert len(declared) == 12
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
@@ -164,3 +164,25 @@ def test_check_offsets_argument_validation_without_gpu(kb):
     assert call(B=-1) == kb.ERR_SHAPE and call(total=-1) == kb.ERR_SHAPE and call(max_len=-1) == kb.ERR_SHAPE
     assert call(off=None) == kb.ERR_NULL and call(out=None) == kb.ERR_NULL
     assert call(off=0x1002) == kb.ERR_ALIGN and call(out=0x1001) == kb.ERR_ALIGN
+
+
+def test_static_scratch_entry_point_validates_on_the_host(kb):
+    """kunlun_gdpa_fwd_static: the checks of kunlun_gdpa_fwd, then its own size limit - all before any device is
+    touched (this test runs without a GPU)."""
+    lib = kb.raw()
+    vp = lambda x: None if x is None else ctypes.c_void_p(x)
+
+    def call(q=0x1000, kvo=0x1000, B=2, d=64, max_q=8, total_q=16, total_kv=100, act=3):
+        return lib.kunlun_gdpa_fwd_static(vp(q), vp(0x1000), vp(0x1000), vp(0x1000), None, None, vp(kvo), B, 2, d, max_q, 64,
+                                          total_q, total_kv, 0.1, act, None, 0, None)
+
+    assert call(q=None) == kb.ERR_NULL
+    assert call(kvo=None) == kb.ERR_NULL
+    assert call(q=0x1004) == kb.ERR_ALIGN
+    assert call(d=60) == kb.ERR_UNSUPPORTED
+    assert call(act=9) == kb.ERR_UNSUPPORTED
+    assert call(total_q=15) == kb.ERR_SHAPE
+    assert call(B=0, total_q=0) == kb.OK
+    big = 200_000
+    assert kb.workspace_bytes(kb.OP_GDPA_FWD, big, 2, 64, 8, 64, big * 8, 100) > kb.STATIC_SCRATCH_BYTES
+    assert call(B=big, total_q=big * 8) == kb.ERR_WORKSPACE
