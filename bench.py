@@ -38,7 +38,7 @@ ORACLE_SAMPLE_EXAMPLES = 256
 # profiles/bench_cfg4_hbm_traffic.txt.  Valid for the default workload and seed only.  (The
 # counters sit between L2 and the memory fabric: re-reads that the 256 MB Infinity Cache serves
 # are included, which is what the sliding-window figure above its algorithmic 9.38 GB shows.)
-MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957138000, "gdpa_bwd": 9780301000, "swa_fwd": 10268127000}
+MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957134000, "gdpa_bwd": 9780146000, "swa_fwd": 10310206000}
 
 
 def device_normal(torch, shape, sigma, seed):
@@ -161,6 +161,8 @@ def main():
     roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": round(achieved / (HBM_PEAK / 1e9), 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if args.seed == 0 else None,
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, taken offline "
+                                  "(profiles/bench_cfg4_hbm_traffic.txt), not measured in this run",
                 "algorithmic_bytes": int(nbytes[dom])}
 
     # The other the benchmark spec workloads (parity-test cases, small): timed separately, no part of
@@ -302,14 +304,23 @@ def main():
 
         # Measured speed of light of this device, by library routines of the harness (torch): a 1 GiB
         # device-to-device copy (read + write) and a large bf16 GEMM.
+        # What this memory system sustains depends on the read : write mix of a stream, so the calls
+        # are put next to plain streaming kernels of their own mix (1 GiB fp32 operands): a sum (reads
+        # only, like gdpa_fwd), a copy (1 : 1, like gdpa_bwd), a + b * c (3 reads : 1 write, like swa_fwd).
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         tw, _ = timed(lambda: flush.copy_(src), n=10)
+        fa, fb = src.view(torch.float32), flush.view(torch.float32)
+        fc, fd = torch.ones_like(fa), torch.empty_like(fa)
+        t31, _ = timed(lambda: torch.addcmul(fa, fb, fc, out=fd), n=10)
+        tr, _ = timed(lambda: torch.sum(fa), n=10)
         ga = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
         gb = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
         tg, _ = timed(lambda: torch.matmul(ga, gb), n=10)
-        other["device_calibration"] = {"copy_1GiB_gbps_read_plus_write": round(2 * (1 << 30) / tw / 1e3, 1),
+        other["device_calibration"] = {"read_only_sum_1GiB_gbps": round((1 << 30) / tr / 1e3, 1),
+                                       "copy_1GiB_gbps_read_plus_write": round(2 * (1 << 30) / tw / 1e3, 1),
+                                       "three_reads_one_write_1GiB_operands_gbps": round(4 * (1 << 30) / t31 / 1e3, 1),
                                        "bf16_gemm_8192_tflops": round(2 * 8192 ** 3 / tg / 1e6, 1)}
-        del src, ga, gb, flush
+        del src, ga, gb, flush, fa, fb, fc, fd
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

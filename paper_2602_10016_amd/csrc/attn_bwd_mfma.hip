@@ -56,7 +56,7 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 31, g = lane >> 5;
     const int64_t hd = (int64_t)p.H * D;
-    const bf16_t* Qg = (const bf16_t*)p.q + q_row0 * hd + (int64_t)h * D;
+    const bf16_t* Qg = (const bf16_t*)p.q + q_src_row(p, q_row0) * hd + (int64_t)h * D;
     const bf16_t* DOg = (const bf16_t*)p.d_o + q_row0 * hd + (int64_t)h * D;
     const bf16_t* Kg = (const bf16_t*)p.k + (k0 * p.H + h) * D;
     const bf16_t* Vg = (const bf16_t*)p.v + (k0 * p.H + h) * D;

@@ -55,7 +55,7 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
     const int64_t hd = (int64_t)p.H * D;
     const uint32_t row_bytes = (uint32_t)(hd * 2);
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
-    const bf16_t* Qg = (const bf16_t*)p.q + q_row0 * hd + (int64_t)h * D;
+    const bf16_t* Qg = (const bf16_t*)p.q + q_src_row(p, q_row0) * hd + (int64_t)h * D;
     const bf16_t* DOg = (const bf16_t*)p.d_o + q_row0 * hd + (int64_t)h * D;
     const char* Kg = (const char*)((const bf16_t*)p.k + (k0 * p.H + h) * D);
     const char* Vg = (const char*)((const bf16_t*)p.v + (k0 * p.H + h) * D);

@@ -187,7 +187,7 @@ __device__ __forceinline__ void bwd_dq_item(const AttnParams& p, float* __restri
     {
         char* own = lds + SM::TOTAL - SM::OWN_BYTES;
         const int64_t goff = q_row0 * hd + (int64_t)h * D;
-        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.q + goff), row_bytes, nq_wg, tid);
+        stage_rows_swizzled<D, NW>(own, (const char*)((const bf16_t*)p.q + q_src_row(p, q_row0) * hd + (int64_t)h * D), row_bytes, nq_wg, tid);
         __syncthreads();
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(own + wave * SM::TILE + L::k_offset(r, 2 * kc + g));
@@ -335,7 +335,7 @@ __device__ __forceinline__ void bwd_dkdv_item(const AttnParams& p, const float* 
     const int64_t hd = (int64_t)p.H * D;
     const uint32_t row_bytes = (uint32_t)(hd * 2);
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
-    const char* Q = (const char*)((const bf16_t*)p.q + (q0 * p.H + h) * D);
+    const char* Q = (const char*)((const bf16_t*)p.q + (q_src_row(p, q0) * p.H + h) * D);
     const char* DO = (const char*)((const bf16_t*)p.d_o + (q0 * p.H + h) * D);
     const uint32_t lds0 = lds_address(lds);
 
@@ -711,7 +711,7 @@ __device__ __forceinline__ void bwd_fewkeys_item(const AttnParams& p, const floa
             // Q and dO straight into LDS (no staging registers); rows past the wave's queries repeat the last
             // one and get zero weight below; a wave without queries loads nothing and computes nothing
             if (nq > 0) {
-                dma.issue((const char*)((const bf16_t*)p.q + rows0 * hd + (int64_t)h * D), nq, lds_address(ldsQ));
+                dma.issue((const char*)((const bf16_t*)p.q + q_src_row(p, rows0) * hd + (int64_t)h * D), nq, lds_address(ldsQ));
                 dma.issue((const char*)((const bf16_t*)p.d_o + rows0 * hd + (int64_t)h * D), nq, lds_address(ldsDO));
             }
         }

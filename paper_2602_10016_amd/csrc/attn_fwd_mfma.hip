@@ -147,7 +147,7 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     static_assert(QT * SM::K_STRIDE <= LDS_BYTES, "query tile must fit the tile buffers");
     bf16x8 qf[NQB][KC];
     {
-        const char* qbase = (const char*)(Q + q_row0 * hd + (int64_t)h * D);
+        const char* qbase = (const char*)(Q + q_src_row(p, q_row0) * hd + (int64_t)h * D);
         const __amdgpu_buffer_rsrc_t qrsrc =
             __builtin_amdgcn_make_buffer_rsrc((void*)qbase, 0, (nq_wg - 1) * (int)row_bytes + D * 2, 0x00020000);
         u32x4 qst[Q_LOADS];

@@ -96,7 +96,7 @@ __device__ __forceinline__ void attn_fwd_ring_item(const AttnParams& p, char* ld
     bf16x8 qf[KC];
     {
         char* qstage = lds + SM::TOTAL - SM::Q_BYTES;
-        stage_rows_swizzled<D, NW>(qstage, (const char*)((const bf16_t*)p.q + q_row0 * hd + (int64_t)h * D), row_bytes, nq_wg, tid);
+        stage_rows_swizzled<D, NW>(qstage, (const char*)((const bf16_t*)p.q + q_src_row(p, q_row0) * hd + (int64_t)h * D), row_bytes, nq_wg, tid);
         __syncthreads();
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc)

@@ -27,6 +27,7 @@ struct AttnParams {
     int64_t total_q, total_kv;
     float scale;
     int windowed, left, right;  // sliding window (self-attention); left/right < 0: unbounded
+    int q_shared;               // 1: q holds ONE block of max_q rows that every example uses (batch-shared seed queries)
     uint8_t head_act[KUNLUN_MAX_HEADS];
 };
 
@@ -84,6 +85,10 @@ __device__ __forceinline__ int64_t q_begin(const AttnParams& p, int b) {
 __device__ __forceinline__ int64_t q_end(const AttnParams& p, int b) {
     return p.q_off ? (int64_t)p.q_off[b + 1] : (int64_t)(b + 1) * p.max_q;
 }
+// Row of the q tensor that holds query `row` (a row of o, d_o, dq and lse, numbered over the whole batch): the
+// same row, unless the batch shares one block of max_q seed queries (dense queries then: example b owns rows
+// b * max_q ..), where it is the row's position inside its example.
+__device__ __forceinline__ int64_t q_src_row(const AttnParams& p, int64_t row) { return p.q_shared ? row % p.max_q : row; }
 
 // Largest b in [0, B) with off[b] <= row (rows of empty examples are skipped naturally).
 __device__ __forceinline__ int find_example(const int32_t* off, int B, int64_t row) {

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(64) void scalar_fwd_kernel(AttnParams p) {
     const T* V = (const T*)p.v;
     T* O = (T*)p.o;
 
-    for (int c = lane; c < d; c += 64) sq[c] = to_float(Q[row * hd + (int64_t)h * d + c]);
+    for (int c = lane; c < d; c += 64) sq[c] = to_float(Q[q_src_row(p, row) * hd + (int64_t)h * d + c]);
     __syncthreads();
 
     int64_t lo, hi;
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64) void scalar_bwd_dq_kernel(AttnParams p) {
 
     float part = 0.f;
     for (int c = lane; c < d; c += 64) {
-        sq[c] = to_float(Q[qbase + c]);
+        sq[c] = to_float(Q[q_src_row(p, row) * hd + (int64_t)h * d + c]);
         sdo[c] = to_float(DO[qbase + c]);
         if (softmax) part = fmaf(sdo[c], to_float(O[qbase + c]), part);
     }
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(64) void scalar_bwd_dkdv_kernel(AttnParams p) {
         float pw = 0.f, ds = 0.f;
         if (i_q <= hi) {
             const int64_t qb = (q0 + i_q) * hd + (int64_t)h * d;
-            const float s = p.scale * row_dot(sk, Q + qb, d);
+            const int64_t qsrc = q_src_row(p, q0 + i_q) * hd + (int64_t)h * d;
+            const float s = p.scale * row_dot(sk, Q + qsrc, d);
             const float dp = row_dot(sv, DO + qb, d);
             if (softmax) {
                 float delta = 0.f;
@@ -239,11 +240,12 @@ __global__ __launch_bounds__(64) void scalar_bwd_dkdv_kernel(AttnParams p) {
         for (int ii = 0; ii < nq; ++ii) {
             const float wp = sp[ii], wds = sds[ii];
             const int64_t qb = (q0 + base + ii) * hd + (int64_t)h * d;
+            const int64_t qsb = q_src_row(p, q0 + base + ii) * hd + (int64_t)h * d;
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 const int c = lane + 64 * i;
                 if (c < d) {
-                    acck[i] = fmaf(wds, to_float(Q[qb + c]), acck[i]);
+                    acck[i] = fmaf(wds, to_float(Q[qsb + c]), acck[i]);
                     accv[i] = fmaf(wp, to_float(DO[qb + c]), accv[i]);
                 }
             }
