@@ -16,6 +16,8 @@
  *                    backward pass that Sec. "Efficient Attention-Style Implementation" and
  *                    App. "GDPA and Fused PFFN Kernel" describe: scores are recomputed
  *                    tile by tile, no score-sized tensor is stored).
+ *   kunlun_seed_attn_fwd / _bwd  The same with one block of seed queries shared by the whole batch
+ *                    (Sec. "Hierarchical Seed Pooling", stage 1) and its gradient summed over the batch.
  *   kunlun_swa_fwd   Sliding-window self-attention, Eq. (sliding window) of Sec. "Sliding
  *                    Window Attention": query t attends to keys [t-left, t+right] of its
  *                    own sequence under softmax.
@@ -85,7 +87,14 @@ typedef enum {
     KUNLUN_ACT_SILU = 5
 } kunlun_act;
 
-typedef enum { KUNLUN_OP_GDPA_FWD = 0, KUNLUN_OP_GDPA_BWD = 1, KUNLUN_OP_SWA_FWD = 2, KUNLUN_OP_SWA_BWD = 3 } kunlun_op;
+typedef enum {
+    KUNLUN_OP_GDPA_FWD = 0,
+    KUNLUN_OP_GDPA_BWD = 1,
+    KUNLUN_OP_SWA_FWD = 2,
+    KUNLUN_OP_SWA_BWD = 3,
+    KUNLUN_OP_SEED_FWD = 4,
+    KUNLUN_OP_SEED_BWD = 5
+} kunlun_op;
 
 #define KUNLUN_MAX_HEADS 64
 
@@ -148,6 +157,35 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
                     const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Seed-level attention with batch-shared seeds (Sec. "Hierarchical Seed Pooling", stage 1: the learnable seed
+ * embeddings "are shared across all samples in the batch"; Eq. (seed-level attention): H_seed = MHA(Norm(E_seed),
+ * S, S)).  The same computation as kunlun_gdpa_fwd with n_seeds dense queries per example, except that the
+ * queries are ONE block
+ *   e_seed   in, device, [n_seeds, H, d]   the projected (and normalised) seed queries, used by every example
+ * instead of a [B * n_seeds, H, d] tensor that repeats it B times; o (out, [B * n_seeds, H, d]) and lse
+ * ([H, B * n_seeds]) are per example as before.  act = KUNLUN_ACT_SOFTMAX is the paper's use; the other score
+ * functions work as well.  Workspace: kunlun_workspace_bytes(KUNLUN_OP_SEED_FWD, B, H, d, n_seeds, max_kv,
+ * B * n_seeds, total_kv).  The normalisation and the query projection of the seeds are the caller's: they act on
+ * the n_seeds x d_model parameter once per step, before the per-head projection, not on anything per example.
+ */
+int kunlun_seed_attn_fwd(const void* e_seed, const void* k, const void* v, void* o, float* lse, const int32_t* kv_offsets, int B,
+                         int H, int d, int n_seeds, int max_kv, int64_t total_kv, float scale, int act, const int32_t* head_act,
+                         int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of kunlun_seed_attn_fwd.  dk, dv as in kunlun_gdpa_bwd;
+ *   d_e   out, device, [n_seeds, H, d]   gradient of the shared seed queries = the sum over the B examples of the
+ *         per-example query gradients dQ_b (Eq. (seed-level attention) with shared E_seed, chain rule).
+ * The dQ_b go to the workspace and are added in a fixed order (examples in groups of 32, each group in example
+ * order, then the groups in order; fp32 sums, rounded once): no atomics, bit-reproducible.  o, lse, d_o:
+ * [B * n_seeds, ...] as in kunlun_gdpa_bwd.  Workspace: kunlun_workspace_bytes(KUNLUN_OP_SEED_BWD, ... as above).
+ */
+int kunlun_seed_attn_bwd(const void* e_seed, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                         void* d_e, void* dk, void* dv, const int32_t* kv_offsets, int B, int H, int d, int n_seeds, int max_kv,
+                         int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/*
  * Sliding-window softmax self-attention over jagged sequences (Eq. (sliding window)).
  * q, k, v, o share `offsets` (device int32 [B+1]) and have `total` rows.  The query at
  * position t of a sequence of length L sees keys max(0, t-window_left) ..
@@ -174,7 +212,7 @@ int kunlun_swa_bwd(const void* q, const void* k, const void* v, const void* o, c
 
 /* Bytes of workspace that a call of `op` (kunlun_op) with these sizes needs.  Returns 0 for
  * an unknown op or negative sizes.  For the sliding-window ops pass max_len as max_q and
- * max_kv and total as total_q and total_kv. */
+ * max_kv and total as total_q and total_kv; for the seed ops n_seeds as max_q and B * n_seeds as total_q. */
 size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
                               int64_t total_kv);
 

@@ -98,6 +98,27 @@ class OracleLib:
             raise ValueError("oracle_gdpa_bwd: unknown activation")
         return dq, dk, dv
 
+    def seed_attn_fwd(self, e_seed, k, v, kv_offsets, scale, act, head_act=None):
+        """Seed-level attention with seeds shared across the batch (Sec. "Hierarchical Seed Pooling", stage 1;
+        Eq. (seed-level attention)): every example uses the same n_seeds query rows.  Written out as the
+        definition: the seed block repeated once per example, then the per-example attention.  Returns (O, LSE)."""
+        e_seed = _f64(e_seed)
+        B = _i32(kv_offsets).size - 1
+        q = np.ascontiguousarray(np.tile(e_seed, (B, 1, 1)))
+        return self.gdpa_fwd(q, k, v, kv_offsets, scale, act, max_q=e_seed.shape[0], head_act=head_act)
+
+    def seed_attn_bwd(self, e_seed, k, v, d_o, kv_offsets, scale, act, head_act=None):
+        """Gradient of <O, dO> of seed_attn_fwd: (dE, dK, dV), where dE is the sum over the examples of the
+        per-example query gradients (the seeds are one shared parameter block)."""
+        e_seed = _f64(e_seed)
+        B = _i32(kv_offsets).size - 1
+        q = np.ascontiguousarray(np.tile(e_seed, (B, 1, 1)))
+        dq, dk, dv = self.gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, max_q=e_seed.shape[0], head_act=head_act)
+        d_e = np.zeros_like(e_seed)
+        for b in range(B):
+            d_e += dq[b * e_seed.shape[0]:(b + 1) * e_seed.shape[0]]
+        return d_e, dk, dv
+
     def swa_fwd(self, q, k, v, offsets, left, right, scale):
         """Sliding-window softmax self-attention; left/right < 0 means unbounded.  Returns (O, LSE)."""
         q, k, v = _f64(q), _f64(k), _f64(v)
@@ -157,6 +178,8 @@ class OracleLib:
 _default = OracleLib(build())
 gdpa_fwd = _default.gdpa_fwd
 gdpa_bwd = _default.gdpa_bwd
+seed_attn_fwd = _default.seed_attn_fwd
+seed_attn_bwd = _default.seed_attn_bwd
 swa_fwd = _default.swa_fwd
 swa_bwd = _default.swa_bwd
 sumkron_fwd = _default.sumkron_fwd

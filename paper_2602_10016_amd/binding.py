@@ -20,8 +20,8 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
 ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
-OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD = 0, 1, 2, 3
-EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
+OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD, OP_SEED_FWD, OP_SEED_BWD = 0, 1, 2, 3, 4, 5
+EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_seed_attn_fwd", "kunlun_seed_attn_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
            "kunlun_check_offsets", "kunlun_strerror"]
 
@@ -35,6 +35,11 @@ STATIC_SCRATCH_BYTES = 1 << 20
 _lib.kunlun_gdpa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64,
                                  _i64, _f, _i, _vp, _i, _vp, _sz, _vp]
 _lib.kunlun_gdpa_bwd.restype = _i
+_lib.kunlun_seed_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _f, _i, _vp, _i, _vp, _sz, _vp]
+_lib.kunlun_seed_attn_fwd.restype = _i
+_lib.kunlun_seed_attn_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _f, _i, _vp, _i,
+                                      _vp, _sz, _vp]
+_lib.kunlun_seed_attn_bwd.restype = _i
 _lib.kunlun_swa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _i, _i, _f, _i, _vp, _sz, _vp]
 _lib.kunlun_swa_fwd.restype = _i
 _lib.kunlun_swa_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _i, _i, _f, _i, _vp,
@@ -246,6 +251,53 @@ def gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, *, o=None, lse=None, q_offset
     if rc != OK:
         raise KunlunError(rc)
     return dq, dk, dv
+
+
+def seed_attn_fwd(e_seed, k, v, kv_offsets, scale, act=ACT_SOFTMAX, *, max_kv, head_act=None, out=None, lse=None,
+                  want_lse=True, workspace=None, stream=None):
+    """kunlun_seed_attn_fwd.  e_seed [n_seeds,H,d] is shared by all examples; returns (o [B*n_seeds,H,d], lse)."""
+    _check_qkv(e_seed, k, v)
+    n_seeds, H, d = e_seed.shape
+    _check_offsets("kv_offsets", kv_offsets)
+    B = kv_offsets.numel() - 1
+    total_q = B * n_seeds
+    o = torch.empty((total_q, H, d), dtype=e_seed.dtype, device=e_seed.device) if out is None else out
+    _check("out", o, like=e_seed, shape=(total_q, H, d))
+    if lse is None and want_lse:
+        lse = torch.empty((H, total_q), dtype=torch.float32, device=e_seed.device)
+    _check("lse", lse, dtype=torch.float32, shape=(H, total_q), optional=True)
+    ha = _head_act(head_act, H)
+    ws = _workspace(workspace, workspace_bytes(OP_SEED_FWD, B, H, d, n_seeds, max_kv, total_q, k.shape[0]), e_seed.device)
+    _on_device(e_seed=e_seed, k=k, v=v, kv_offsets=kv_offsets, out=o, lse=lse, workspace=ws)
+    rc = _lib.kunlun_seed_attn_fwd(_ptr(e_seed), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(kv_offsets), B, H, d, n_seeds,
+                                   int(max_kv), k.shape[0], float(scale), int(act), ha, _dtype_code(e_seed), _ptr(ws), ws.numel(),
+                                   _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return o, lse
+
+
+def seed_attn_bwd(e_seed, k, v, d_o, kv_offsets, scale, act=ACT_SOFTMAX, *, o=None, lse=None, max_kv, head_act=None, out=None,
+                  workspace=None, stream=None):
+    """kunlun_seed_attn_bwd.  Returns (d_e [n_seeds,H,d], dk, dv); o and lse are the forward results."""
+    _check_qkv(e_seed, k, v)
+    n_seeds, H, d = e_seed.shape
+    _check_offsets("kv_offsets", kv_offsets)
+    B = kv_offsets.numel() - 1
+    total_q = B * n_seeds
+    _check("d_o", d_o, like=e_seed, shape=(total_q, H, d))
+    _check("o", o, like=e_seed, shape=(total_q, H, d), optional=True)
+    _check("lse", lse, dtype=torch.float32, shape=(H, total_q), optional=True)
+    d_e, dk, dv = _grads(out, e_seed, k, v)
+    ha = _head_act(head_act, H)
+    ws = _workspace(workspace, workspace_bytes(OP_SEED_BWD, B, H, d, n_seeds, max_kv, total_q, k.shape[0]), e_seed.device)
+    _on_device(e_seed=e_seed, k=k, v=v, d_o=d_o, o=o, lse=lse, kv_offsets=kv_offsets, d_e=d_e, dk=dk, dv=dv, workspace=ws)
+    rc = _lib.kunlun_seed_attn_bwd(_ptr(e_seed), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_e), _ptr(dk), _ptr(dv),
+                                   _ptr(kv_offsets), B, H, d, n_seeds, int(max_kv), k.shape[0], float(scale), int(act), ha,
+                                   _dtype_code(e_seed), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+    return d_e, dk, dv
 
 
 def swa_fwd(q, k, v, offsets, window_left, window_right, scale, *, max_len, out=None, lse=None, want_lse=True,

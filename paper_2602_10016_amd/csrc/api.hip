@@ -38,6 +38,11 @@ int fill_acts(AttnParams& p, int H, int act, const int32_t* head_act, bool& any_
 
 size_t order_bytes(int B) { return align_up((size_t)(B + 1) * sizeof(int32_t), 256); }
 
+int gdpa_bwd_checked(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o, void* dq,
+                     void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H, int d, int max_q,
+                     int max_kv, int64_t total_q, int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype,
+                     void* workspace, size_t workspace_bytes, void* stream, bool q_shared);
+
 }  // namespace
 
 extern "C" {
@@ -48,7 +53,11 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
     switch (op) {
     case KUNLUN_OP_GDPA_FWD:
     case KUNLUN_OP_SWA_FWD:
+    case KUNLUN_OP_SEED_FWD:
         return WS_HEADER_BYTES + tile_table_bytes(B, total_q);
+    case KUNLUN_OP_SEED_BWD:  // + the per-example query gradients (at most 4 bytes per element) and the partial sums over the batch
+        return kunlun_workspace_bytes(KUNLUN_OP_GDPA_BWD, B, H, d, max_q, max_kv, total_q, total_kv) +
+               seed_grad_rows_bytes(total_q, H, d, KUNLUN_FP32) + seed_grad_partial_bytes(B, (int64_t)max_q * H * d);
     case KUNLUN_OP_GDPA_BWD:
     case KUNLUN_OP_SWA_BWD:
         return WS_HEADER_BYTES + order_bytes(B) +
@@ -130,7 +139,15 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
                     int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
                     size_t workspace_bytes, void* stream) {
     return kunlun::gdpa_fwd_checked(q, k, v, o, lse, q_offsets, kv_offsets, B, H, d, max_q, max_kv, total_q, total_kv, scale, act,
-                                    head_act, dtype, workspace, workspace_bytes, stream, true);
+                                    head_act, dtype, workspace, workspace_bytes, stream, true, false);
+}
+
+int kunlun_seed_attn_fwd(const void* e_seed, const void* k, const void* v, void* o, float* lse, const int32_t* kv_offsets, int B,
+                         int H, int d, int n_seeds, int max_kv, int64_t total_kv, float scale, int act, const int32_t* head_act,
+                         int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_seeds < 0 || B < 0) return KUNLUN_ERR_SHAPE;
+    return kunlun::gdpa_fwd_checked(e_seed, k, v, o, lse, nullptr, kv_offsets, B, H, d, n_seeds, max_kv, (int64_t)B * n_seeds,
+                                    total_kv, scale, act, head_act, dtype, workspace, workspace_bytes, stream, true, true);
 }
 
 }  // extern "C"
@@ -140,7 +157,7 @@ int kunlun_gdpa_fwd(const void* q, const void* k, const void* v, void* o, float*
 int kunlun::gdpa_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
                              const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q,
                              int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
-                             size_t workspace_bytes, void* stream, bool launch) {
+                             size_t workspace_bytes, void* stream, bool launch, bool q_shared) {
     int rc = check_common(B, H, d, max_q, max_kv, total_q, total_kv, scale, dtype);
     if (rc != KUNLUN_OK) return rc;
     AttnParams p;
@@ -165,6 +182,7 @@ int kunlun::gdpa_fwd_checked(const void* q, const void* k, const void* v, void* 
     p.B = B; p.H = H; p.d = d; p.max_q = max_q; p.max_kv = max_kv;
     p.total_q = total_q; p.total_kv = total_kv; p.scale = scale;
     p.windowed = 0; p.left = -1; p.right = -1;
+    p.q_shared = q_shared ? 1 : 0;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (mfma_fwd_supported(p, dtype)) {
@@ -192,6 +210,28 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
                     void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H,
                     int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, float scale, int act,
                     const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return gdpa_bwd_checked(q, k, v, o, lse, d_o, dq, dk, dv, q_offsets, kv_offsets, B, H, d, max_q, max_kv, total_q, total_kv,
+                            scale, act, head_act, dtype, workspace, workspace_bytes, stream, false);
+}
+
+int kunlun_seed_attn_bwd(const void* e_seed, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                         void* d_e, void* dk, void* dv, const int32_t* kv_offsets, int B, int H, int d, int n_seeds, int max_kv,
+                         int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (n_seeds < 0 || B < 0) return KUNLUN_ERR_SHAPE;
+    return gdpa_bwd_checked(e_seed, k, v, o, lse, d_o, d_e, dk, dv, nullptr, kv_offsets, B, H, d, n_seeds, max_kv,
+                            (int64_t)B * n_seeds, total_kv, scale, act, head_act, dtype, workspace, workspace_bytes, stream, true);
+}
+
+}  // extern "C"
+
+namespace {
+// kunlun_gdpa_bwd proper.  q_shared: q is one block of max_q seed rows used by every example and dq receives the
+// gradient of that block, the sum over the batch of the per-example query gradients (which go to the workspace).
+int gdpa_bwd_checked(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* d_o,
+                     void* dq, void* dk, void* dv, const int32_t* q_offsets, const int32_t* kv_offsets, int B, int H,
+                     int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv, float scale, int act,
+                     const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes, void* stream, bool q_shared) {
     int rc = check_common(B, H, d, max_q, max_kv, total_q, total_kv, scale, dtype);
     if (rc != KUNLUN_OK) return rc;
     AttnParams p;
@@ -209,7 +249,9 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
         !aligned(dq, 16) || !aligned(dk, 16) || !aligned(dv, 16) || !aligned(lse, 4) || !aligned(q_offsets, 4) ||
         !aligned(kv_offsets, 4))
         return KUNLUN_ERR_ALIGN;
-    if (!workspace || workspace_bytes < kunlun_workspace_bytes(KUNLUN_OP_GDPA_BWD, B, H, d, max_q, max_kv, total_q, total_kv))
+    const size_t base_bytes = kunlun_workspace_bytes(KUNLUN_OP_GDPA_BWD, B, H, d, max_q, max_kv, total_q, total_kv);
+    if (!workspace || workspace_bytes < (q_shared ? kunlun_workspace_bytes(KUNLUN_OP_SEED_BWD, B, H, d, max_q, max_kv, total_q, total_kv)
+                                                  : base_bytes))
         return KUNLUN_ERR_WORKSPACE;
     if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
 
@@ -221,6 +263,14 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
     p.windowed = 0; p.left = -1; p.right = -1;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
+    // shared seed queries: the kernels leave the per-example query gradients in the workspace (behind what the
+    // call needs anyway); the sum over the batch follows below
+    char* const dq_all = (char*)workspace + base_bytes;
+    const size_t dq_all_bytes = seed_grad_rows_bytes(total_q, H, d, dtype);
+    if (q_shared) {
+        p.q_shared = 1;
+        p.dq = dq_all;
+    }
     if (mfma_bwd_supported(p, dtype)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
         if (schedule_is_moot((int64_t)B * H, d == 128 ? (max_q > 32 ? 2 : 1) : 4)) {  // workgroups of the kernel per compute unit
@@ -236,8 +286,13 @@ int kunlun_gdpa_bwd(const void* q, const void* k, const void* v, const void* o, 
     } else {
         e = launch_scalar_bwd(p, dtype, s);
     }
+    if (e == hipSuccess && q_shared && total_q > 0)
+        e = launch_seed_grad_sum(dq_all, dq, (float*)(dq_all + dq_all_bytes), B, (int64_t)max_q * H * d, dtype, s);
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
+}  // namespace
+
+extern "C" {
 
 int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* offsets, int B,
                    int H, int d, int max_len, int64_t total, int window_left, int window_right, float scale,

@@ -39,7 +39,19 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int gdpa_fwd_checked(const void* q, const void* k, const void* v, void* o, float* lse, const int32_t* q_offsets,
                      const int32_t* kv_offsets, int B, int H, int d, int max_q, int max_kv, int64_t total_q, int64_t total_kv,
                      float scale, int act, const int32_t* head_act, int dtype, void* workspace, size_t workspace_bytes,
-                     void* stream, bool launch);
+                     void* stream, bool launch, bool q_shared);
+
+// Gradient of batch-shared seed queries: d_e[n] = sum over the B examples of rows[b * n_elems + n] (rows: the
+// per-example query gradients, `dtype` elements), in a fixed order - examples in groups of SEED_GROUP, each group
+// summed in example order into an fp32 partial sum, the partial sums added in group order, rounded once.
+constexpr int SEED_GROUP = 32;
+inline size_t seed_grad_rows_bytes(int64_t total_q, int H, int d, int dtype) {
+    return align_up((size_t)total_q * H * d * (dtype == KUNLUN_FP32 ? 4 : 2), 256);
+}
+inline size_t seed_grad_partial_bytes(int B, int64_t n_elems) {
+    return align_up((size_t)((B + SEED_GROUP - 1) / SEED_GROUP) * n_elems * sizeof(float), 256);
+}
+hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int B, int64_t n_elems, int dtype, hipStream_t stream);
 
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);

@@ -89,3 +89,45 @@ hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* or
 }
 
 }  // namespace kunlun
+
+namespace kunlun {
+
+// ---- gradient of batch-shared seed queries (Sec. "Hierarchical Seed Pooling", stage 1: the learnable seeds are
+// shared by all examples, so their gradient is the sum of the per-example query gradients).  No atomics: the
+// order of every addition is fixed by (group, example), so the result does not depend on the launch.
+template <typename T>
+__global__ __launch_bounds__(256) void seed_grad_group_kernel(const T* __restrict__ rows, float* __restrict__ partial, int B,
+                                                              int64_t n_elems) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int group = blockIdx.y;
+    if (n >= n_elems) return;
+    const int b0 = group * SEED_GROUP, b1 = b0 + SEED_GROUP < B ? b0 + SEED_GROUP : B;
+    float acc = 0.f;
+    for (int b = b0; b < b1; ++b) acc += to_float(rows[(int64_t)b * n_elems + n]);
+    partial[(int64_t)group * n_elems + n] = acc;
+}
+template <typename T>
+__global__ __launch_bounds__(256) void seed_grad_final_kernel(const float* __restrict__ partial, T* __restrict__ d_e, int groups,
+                                                              int64_t n_elems) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_elems) return;
+    float acc = 0.f;
+    for (int g = 0; g < groups; ++g) acc += partial[(int64_t)g * n_elems + n];
+    d_e[n] = from_float<T>(acc);
+}
+
+hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int B, int64_t n_elems, int dtype, hipStream_t stream) {
+    if (n_elems <= 0) return hipSuccess;
+    const int groups = (B + SEED_GROUP - 1) / SEED_GROUP;
+    const dim3 grid1((unsigned)((n_elems + 255) / 256), (unsigned)groups), grid2((unsigned)((n_elems + 255) / 256));
+    if (dtype == KUNLUN_FP32) {
+        hipLaunchKernelGGL(seed_grad_group_kernel<float>, grid1, dim3(256), 0, stream, (const float*)rows, partial, B, n_elems);
+        hipLaunchKernelGGL(seed_grad_final_kernel<float>, grid2, dim3(256), 0, stream, partial, (float*)d_e, groups, n_elems);
+    } else {
+        hipLaunchKernelGGL(seed_grad_group_kernel<bf16_t>, grid1, dim3(256), 0, stream, (const bf16_t*)rows, partial, B, n_elems);
+        hipLaunchKernelGGL(seed_grad_final_kernel<bf16_t>, grid2, dim3(256), 0, stream, partial, (bf16_t*)d_e, groups, n_elems);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace kunlun

@@ -42,7 +42,7 @@ extern "C" int kunlun_gdpa_fwd_static(const void* q, const void* k, const void* 
                                       int64_t total_kv, float scale, int act, const int32_t* head_act, int dtype, void* stream) {
     // every check of kunlun_gdpa_fwd first, against a stand-in workspace of the full size (host only) ...
     int rc = kunlun::gdpa_fwd_checked(q, k, v, o, lse, q_offsets, kv_offsets, B, H, d, max_q, max_kv, total_q, total_kv, scale,
-                                      act, head_act, dtype, (void*)(uintptr_t)256, (size_t)-1, stream, false);
+                                      act, head_act, dtype, (void*)(uintptr_t)256, (size_t)-1, stream, false, false);
     if (rc != KUNLUN_OK) return rc;
     if (B == 0 || total_q == 0) return KUNLUN_OK;
     // ... then the one limit of this entry point: the work lists must fit the fixed array
@@ -53,5 +53,5 @@ extern "C" int kunlun_gdpa_fwd_static(const void* q, const void* k, const void* 
     // The kernels overwrite every entry of the work lists they read, so nothing in the array has to start at
     // zero and no fill is enqueued; whatever the previous call left behind is dead.
     return kunlun::gdpa_fwd_checked(q, k, v, o, lse, q_offsets, kv_offsets, B, H, d, max_q, max_kv, total_q, total_kv, scale, act,
-                                    head_act, dtype, ws, (size_t)KUNLUN_STATIC_SCRATCH_BYTES, stream, true);
+                                    head_act, dtype, ws, (size_t)KUNLUN_STATIC_SCRATCH_BYTES, stream, true, false);
 }

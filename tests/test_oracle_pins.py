@@ -369,6 +369,40 @@ def test_swa_backward_finite_differences(oracle, window):
     _fd_check(fwd, grads, [q, k, v], d_o)
 
 
+@pytest.mark.parametrize("act", ["softmax", "gelu"])
+def test_shared_seed_attention_vs_library_and_finite_differences(oracle, act):
+    """Seeds shared across the batch (Sec. "Hierarchical Seed Pooling", stage 1): forward against torch fp64
+    attention per example with ONE seed tensor, the seed gradient against autograd through that shared tensor
+    (softmax) and against central finite differences of the shared block (both score functions)."""
+    rng = np.random.default_rng(23)
+    lens, n_seeds, H, d = [5, 0, 9, 1], 3, 2, 4
+    _, k, v, _, kv_off = rand_problem(rng, [n_seeds] * len(lens), lens, H, d)
+    e = rng.standard_normal((n_seeds, H, d))
+    d_o = rng.standard_normal((len(lens) * n_seeds, H, d))
+    scale = 0.7
+    o, _ = oracle.seed_attn_fwd(e, k, v, kv_off, scale, ACTS[act])
+    d_e, dk, dv = oracle.seed_attn_bwd(e, k, v, d_o, kv_off, scale, ACTS[act])
+    assert d_e.shape == e.shape
+    fwd = lambda a, b, c: oracle.seed_attn_fwd(a, b, c, kv_off, scale, ACTS[act])[0]
+    _fd_check(fwd, (d_e, dk, dv), [e, k, v], d_o)
+    if act == "softmax":
+        te, tk, tv = [torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (e, k, v)]
+        outs = []
+        for b, L in enumerate(lens):
+            ks = slice(int(kv_off[b]), int(kv_off[b + 1]))
+            if L == 0:
+                outs.append(torch.zeros((n_seeds, H, d), dtype=torch.float64))
+                continue
+            att = torch.nn.functional.scaled_dot_product_attention(te.transpose(0, 1), tk[ks].transpose(0, 1), tv[ks].transpose(0, 1),
+                                                                   scale=scale)
+            outs.append(att.transpose(0, 1))
+        to = torch.cat(outs)
+        np.testing.assert_allclose(o, to.detach().numpy(), rtol=1e-11, atol=1e-12)
+        (to * torch.tensor(d_o)).sum().backward()
+        np.testing.assert_allclose(d_e, te.grad.numpy(), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(dk, tk.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
 # ---------- invariants ----------
 
 @pytest.mark.parametrize("act", ["softmax", "gelu"])
