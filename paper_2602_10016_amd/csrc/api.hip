@@ -322,7 +322,13 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
     p.right = (window_right < 0 || window_right >= max_len) ? -1 : window_right;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
-    if (mfma_fwd_supported(p, dtype)) {
+    if (mfma_fwd_supported(p, dtype) && swa_band_applies(p)) {
+        int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);  // sequences, longest first
+        e = launch_schedule(offsets, B, max_len, order, s);
+        if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
+        p.order = order;
+        e = launch_swa_band_fwd(p, s);
+    } else if (mfma_fwd_supported(p, dtype)) {
         p.order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);  // holds the query-tile prefix sums
         e = launch_mfma_fwd(p, s);
     } else {

@@ -1,0 +1,330 @@
+// bf16 matrix-core forward kernel for sliding-window self-attention with a bounded window (Eq. (sliding
+// window)), gfx950: one workgroup walks one (sequence, head) from its first key tile to its last.
+//
+// A query block (32 queries) needs the key tiles (32 keys) first(j) .. last(j) of its window, and consecutive
+// blocks need consecutive, overlapping ranges: tile t is wanted by the blocks t - c_r .. t + c_l
+// (c_l = ceil(left / 32), c_r = floor((31 + right) / 32)).  So the key tiles of the sequence stream ONCE through
+// a ring of LDS stages, and at every step the c_l + c_r + 1 blocks whose windows cover the tile in flight work
+// on it, each in a wave of its own.  When a block's last tile has passed, its wave writes the block's output
+// rows during the next step and then takes the next unassigned block (block j runs in compute wave j mod NWC,
+// NWC >= c_l + c_r + 2).  Against one workgroup per 128-query tile this removes the steps in which a wave only
+// waits for the other waves' windows, lets output and query staging overlap with the other waves' arithmetic,
+// and fetches every key / value row exactly once per (sequence, head).  It is the outer-loop pipelining of
+// App. "GDPA and Fused PFFN Kernel" (work of consecutive outer iterations overlapped because the inner loops
+// are short), arranged for 64-wide waves that share one compute unit's LDS.
+//
+// Wave 0 is the loader (it computes nothing): it sends key / value tiles ahead into a ring of four LDS stages by
+// buffer-load-to-LDS (lds_ring.h), counts its own loads (they complete in issue order) and publishes the number
+// of tiles that have landed in an LDS word.  The waves of the workgroup do NOT meet at barriers in the key loop:
+// a barrier per step would put every wave into the same phase at the same time (all on the matrix cores, then
+// all on the vector ALU: measured 3.0 ms at the bench size, 2.3 ms with two shifted groups of waves), whereas
+// waves that drift apart by a tile or two overlap the matrix-core phase of one with the vector phase of
+// another on their SIMD.  Instead a compute wave waits (bounded polling of the LDS word) until its tile has
+// landed, and publishes its own progress - the first tile it may still read - in a word of its own; the loader
+// reuses a stage once every compute wave is past the tile it held.  Compute wave w owns query slot w: it loads
+// the query rows of its next block there itself (load-to-LDS, issued as soon as the previous block's output
+// rows have gone out through the same slot) and waits for them on its own counter.
+//
+// Per tile and compute wave the arithmetic is that of the other forward kernels (S^T = K Q^T, online softmax
+// in registers, O^T += V^T P^T through transposing LDS reads).
+#include "attn_fwd_score.h"
+#include "lds_ring.h"
+
+namespace kunlun {
+
+template <int D, int NWC>
+struct BandSmem {
+    static constexpr int ROW = D * 2;
+    static constexpr int TILE = KT * ROW;           // 32 rows of K, of V, or of a query block
+    static constexpr int STAGE = 2 * TILE;          // K tile, then V tile
+    static constexpr int R = 4;                     // ring stages
+    static constexpr int QSLOTS = R * STAGE;        // one slot per compute wave: its block's query rows, later its output rows
+    static constexpr int FLAGS = QSLOTS + NWC * TILE;  // int32: [0] tiles landed, [1 + w] first tile compute wave w may still read
+    static constexpr int TOTAL = FLAGS + 64;
+    static_assert(TOTAL <= 160 * 1024, "one workgroup may use the whole LDS of a compute unit, not more");
+};
+
+constexpr int BAND_MAX_COMPUTE_WAVES = 11;
+
+// Blocks and tiles of one sequence of n rows under the window (left, right), both >= 0.
+struct BandPlan {
+    int n, left, right, n_tiles;
+    __device__ __forceinline__ int first(int j) const { const int lo = 32 * j - left; return lo > 0 ? lo / KT : 0; }
+    __device__ __forceinline__ int last(int j) const {
+        int t_hi = 32 * j + 31;
+        t_hi = t_hi < n - 1 ? t_hi : n - 1;
+        const int64_t hi = (int64_t)t_hi + right;
+        return (int)((hi < n - 1 ? hi : n - 1) / KT);
+    }
+};
+
+// How long a wave polls an LDS word before it gives up (a few milliseconds): the waits below always end
+// - the loader never waits for a tile that a compute wave still needs, see the kernel - and the bound only
+// guarantees that a mistake in that reasoning would show as wrong numbers and not as a wave that never exits.
+constexpr int BAND_SPIN_LIMIT = 1 << 16;
+
+template <int D, int NWC>
+__global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnParams p) {
+    using SM = BandSmem<D, NWC>;
+    using L = TileLayout<D>;
+    constexpr int KC = D / 16, DB = D / 32, CHUNKS = D / 8;
+    constexpr int TI = 2 * TileDma<D, 1, SWZ_K>::INSTR;  // load instructions of a key / value tile pair
+    constexpr int QI = TileDma<D, 1, SWZ_K>::INSTR;      // ... of a query block
+    constexpr int RPI = TileDma<D, 1, SWZ_K>::RPI;       // rows per load instruction
+    static_assert(2 * TI < 64 && SM::R >= 3, "two tiles in flight: their loads must fit the vmcnt counter, their stages the ring");
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    // ---- the work item: workgroup i runs on XCD i % 8; consecutive sequences go to consecutive XCDs and each XCD
+    // walks all heads of its sequences (all L2 channels in use), sequences in scheduler order (longest first)
+    const int xcd = blockIdx.x & 7;
+    const int64_t jj = blockIdx.x >> 3;
+    const int h = (int)(jj % p.H);
+    const int64_t e = (jj / p.H) * 8 + xcd;
+    if (e >= p.B) return;
+    const int b = p.order ? p.order[e] : (int)e;
+    const int64_t row0 = p.kv_off[b];
+    const int n = p.kv_off[b + 1] - (int)row0;
+    if (n <= 0) return;
+    BandPlan plan;
+    plan.n = n; plan.left = p.left; plan.right = p.right; plan.n_tiles = (n + KT - 1) / KT;
+    const int NT = plan.n_tiles, NB = plan.n_tiles;  // key tiles, query blocks
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t hd = (int64_t)p.H * D;
+    const uint32_t row_bytes = (uint32_t)(hd * 2);
+    const int64_t tile_bytes = (int64_t)KT * row_bytes;
+    const uint32_t lds0 = lds_address(lds);
+    volatile int* const flags = (volatile int*)(lds + SM::FLAGS);
+
+    // the words start at "nothing landed, nothing read"; the only barrier of the kernel orders that before any wait
+    if (tid <= NWC) flags[tid] = 0;
+    __syncthreads();
+
+    if (wave == 0) {
+        // ================= loader =================
+        const char* K = (const char*)((const bf16_t*)p.k + (row0 * p.H + h) * D);
+        const char* V = (const char*)((const bf16_t*)p.v + (row0 * p.H + h) * D);
+        TileDma<D, 1, SWZ_K> kdma;
+        TileDma<D, 1, SWZ_V> vdma;
+        kdma.init(lane, 0, row_bytes);
+        vdma.init(lane, 0, row_bytes);
+        for (int t = 0; t < NT; ++t) {
+            // tiles t - 2 and t - 1 are in flight: once t - 2 has landed it is published, before anything else, so
+            // that waves ahead of the others are not held up by the wait below
+            if (t >= 2) {
+                wait_vmcnt<TI>();
+                asm volatile("" ::: "memory");
+                if (lane == 0) flags[0] = t - 1;
+            }
+            if (t >= SM::R) {
+                // the stage of tile t - R: every compute wave must be past that tile.  (It will be: a wave that is not
+                // has its tile in LDS already - tiles up to t - 2 have been published - and needs nothing from here.)
+                const int need = t - SM::R + 1;
+                for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
+                    const int prog = lane < NWC ? flags[1 + lane] : need;
+                    if (__builtin_amdgcn_ballot_w64(prog < need) == 0) break;
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                asm volatile("" ::: "memory");  // the loads below stay behind the poll
+            }
+            const uint32_t dst = lds0 + (t % SM::R) * SM::STAGE;
+            kdma.issue(K + t * tile_bytes, n - t * KT, dst);
+            vdma.issue(V + t * tile_bytes, n - t * KT, dst + SM::TILE);
+        }
+        if (NT >= 2) {
+            wait_vmcnt<TI>();
+            asm volatile("" ::: "memory");
+            if (lane == 0) flags[0] = NT - 1;
+        }
+        wait_vmcnt<0>();
+        asm volatile("" ::: "memory");
+        if (lane == 0) flags[0] = NT;
+        return;
+    }
+
+    // ================= compute waves =================
+    const int cw = wave - 1;
+    const int r = lane & 31, g = lane >> 5;
+    const float sc = p.scale * LOG2E;
+    const int k_rd = L::k_offset(r, g);
+    const int v_rd = SM::TILE + L::v_offset(4 * g + ((lane & 15) >> 2), (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+    char* const slot = lds + SM::QSLOTS + cw * SM::TILE;
+
+    bf16x8 qf[KC];
+    f32x16 oacc[DB][1];
+    float m_ref = -INFINITY, l_run = 0.f;
+    int key_lo = 0x3fffffff;
+    unsigned key_span = 0u;
+    int nq = 0;  // queries of the current block
+
+    // Query rows of block j -> this wave's slot (K-tile swizzle), asynchronously; counted by this wave's vmcnt.
+    // (The lane index passes through an empty volatile statement so that the address arithmetic of these rarely
+    // executed blocks is done in place and not kept in registers across the key loop.)
+    auto load_query_block = [&](int j) {
+        int lane_w = lane;
+        asm volatile("" : "+v"(lane_w));
+        const int rows = n - KT * j < KT ? n - KT * j : KT;
+        const char* src = (const char*)((const bf16_t*)p.q + ((row0 + (int64_t)KT * j) * p.H + h) * D);
+        u32x4 rsrc = make_rsrc_words(src, (uint32_t)(rows - 1) * row_bytes + SM::ROW);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rsrc[i] = __builtin_amdgcn_readfirstlane(rsrc[i]);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_address(slot));
+#pragma unroll
+        for (int i = 0; i < QI; ++i) {
+            const int row = i * RPI + lane_w / CHUNKS;
+            const uint32_t rb = (uint32_t)(row < rows ? row : rows - 1) * row_bytes;  // rows past the end repeat the last one
+            load_to_lds_b128(rsrc, rb + (((lane_w % CHUNKS) ^ swizzle_of_row<D, SWZ_K>(row)) << 4), 0, dst + i * 1024);
+        }
+    };
+    // lane holds query r, channels 32*db + 8*(v/4) + 4g + (v%4): transposed through the wave's slot (16-byte chunks
+    // of a row XOR-swizzled by the row) and written as whole rows
+    auto write_block = [&](int j) {
+        int lane_w = lane;
+        asm volatile("" : "+v"(lane_w));
+        const int r = lane_w & 31, g = lane_w >> 5;
+        const float l_tot = halves_sum(l_run);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        const int64_t grow = row0 + (int64_t)KT * j;  // first row of the block in the packed tensors
+        if (p.lse && g == 0 && r < nq)
+            p.lse[(int64_t)h * p.total_q + grow + r] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                bf16x4 out;
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) out[e4] = (bf16_t)(oacc[db][0][4 * vg + e4] * inv);
+                *(bf16x4*)(slot + r * SM::ROW + (((4 * db + vg) ^ (r & (CHUNKS - 1))) << 4) + 8 * g) = out;
+            }
+        bf16_t* obase = (bf16_t*)p.o + grow * hd + (int64_t)h * D;
+        constexpr int O_STORES = 32 * CHUNKS / 64;
+        const int chunk = lane_w % CHUNKS, rsub = lane_w / CHUNKS;
+#pragma unroll
+        for (int i = 0; i < O_STORES; ++i) {
+            const int row = i * (64 / CHUNKS) + rsub;
+            const u32x4 val = *(const u32x4*)(slot + row * SM::ROW + ((chunk ^ (row & (CHUNKS - 1))) << 4));
+            if (row < nq) __builtin_nontemporal_store(val, (u32x4*)(obase + row * hd + chunk * 8));
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the slot has been read, it may take the next query block
+    };
+
+    // this wave's blocks: cw, cw + NWC, ...
+    for (int jc = cw; jc < NB; jc += NWC) {
+        const int fj = plan.first(jc), ej = plan.last(jc);
+        // from here on this wave reads no tile before fj
+        if (lane == 0) flags[1 + cw] = fj;
+        load_query_block(jc);
+        wait_vmcnt<0>();  // (also the output rows of the previous block, which are older)
+        asm volatile("" ::: "memory");
+        // B-operand fragments (column = query r, contraction = channels 16*kc + 8g ..)
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(slot + (k_rd ^ (kc << 5)));  // = k_offset(r, 2 kc + g)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[db][0][v] = 0.f;
+        m_ref = -INFINITY; l_run = 0.f;
+        nq = n - KT * jc;
+        nq = nq > KT ? KT : nq;
+        {
+            const int tq = KT * jc + r;  // this lane's query (inside the sequence)
+            int lo = tq - p.left, hi = n - 1;
+            lo = lo > 0 ? lo : 0;
+            if ((int64_t)tq + p.right < hi) hi = tq + p.right;
+            const bool empty = hi < lo || r >= nq;
+            key_lo = empty ? 0x3fffffff : lo;
+            key_span = empty ? 0u : (unsigned)(hi - lo);
+        }
+        for (int s = fj; s <= ej; ++s) {
+            // tile s has landed?  (lane 0 polls, the branch is uniform)
+            for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
+                const int landed = __builtin_amdgcn_readfirstlane(flags[0]);
+                if (landed > s) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            asm volatile("" ::: "memory");  // the tile reads below stay behind the poll
+            const char* st = lds + (s % SM::R) * SM::STAGE;
+            // ---- S^T = K Q^T
+            f32x16 sacc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 a = *(const bf16x8*)(st + (k_rd ^ (kc << 5)));
+                sacc = mfma32(a, qf[kc], sacc);
+            }
+            // ---- online softmax; only tiles that some query of the block sees partly take the masked path
+            const int key_base = s * KT;
+            const int tq_lo = KT * jc, tq_hi = KT * jc + nq - 1;
+            bool need_mask = key_base + KT > n || nq < KT;
+            if (key_base < tq_hi - p.left) need_mask = true;
+            if ((int64_t)key_base + KT - 1 > (int64_t)tq_lo + p.right) need_mask = true;
+            bf16x8 pf[2];
+            score_to_weights<KUNLUN_ACT_SOFTMAX, DB, 1>(sacc, need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref,
+                                                        l_run, oacc, 0, pf);
+            // ---- O^T += V^T P^T
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const char* src = st + (v_rd ^ (db << 6)) + c * 16 * SM::ROW;
+                    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src));
+                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * SM::ROW));
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+                    oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
+                }
+            }
+            // every LDS read of tile s has been issued (the LDS serves a wave's operations in order, and the empty
+            // statement keeps the compiler from moving the store up): publish
+            asm volatile("" ::: "memory");
+            if (lane == 0) flags[1 + cw] = s + 1;
+        }
+        write_block(jc);
+    }
+    // no further block: this wave holds back no stage
+    if (lane == 0) flags[1 + cw] = 0x7fffffff;
+}
+
+// The window must be bounded on both sides and narrow enough for the compute waves of one workgroup:
+// c_l + c_r + 2 <= BAND_MAX_COMPUTE_WAVES (see the header of this file).
+static int band_compute_waves(int left, int right) {
+    if (left < 0 || right < 0) return 0;
+    const int64_t c_l = ((int64_t)left + 31) / 32, c_r = ((int64_t)right + 31) / 32;
+    const int64_t need = c_l + c_r + 2;
+    if (need > BAND_MAX_COMPUTE_WAVES || c_l + c_r + 2 > BAND_MAX_COMPUTE_WAVES) return 0;
+    return (int)need;
+}
+
+// Worth it when the window keeps most waves of a compute unit busy (wide enough) and the launch has enough
+// (sequence, head) items for one workgroup per compute unit to balance (one item at a time per compute unit).
+bool swa_band_applies(const AttnParams& p) {
+    const int nwc = band_compute_waves(p.left, p.right);
+    return p.windowed && nwc >= 8 && (int64_t)p.B * p.H >= 8 * 256 && (p.d == 128 || p.d == 64 || p.d == 32) && p.scale > 0.f;
+}
+
+template <int D, int NWC>
+static hipError_t launch_band(const AttnParams& p, hipStream_t stream) {
+    constexpr int bytes = BandSmem<D, NWC>::TOTAL;
+    auto kern = swa_band_fwd_kernel<D, NWC>;
+    if (bytes > 64 * 1024) {
+        // once per process (thread-safe initialisation of a function-local static); not a stream operation
+        static const hipError_t raised = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (raised != hipSuccess) return raised;
+    }
+    const unsigned grid = (unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * (NWC + 1)), bytes, stream, p);
+    return hipGetLastError();
+}
+
+// p.order: the sequences, longest first (written by the scheduler kernel), or null.
+hipError_t launch_swa_band_fwd(const AttnParams& p, hipStream_t stream) {
+    const int nwc = band_compute_waves(p.left, p.right);
+    // two workgroup sizes: up to 9 or up to 11 compute waves (a wave without a block only passes the barriers)
+    if (nwc <= 9)
+        return p.d == 128 ? launch_band<128, 9>(p, stream) : p.d == 64 ? launch_band<64, 9>(p, stream) : launch_band<32, 9>(p, stream);
+    return p.d == 128 ? launch_band<128, 11>(p, stream) : p.d == 64 ? launch_band<64, 11>(p, stream) : launch_band<32, 11>(p, stream);
+}
+
+}  // namespace kunlun

@@ -69,6 +69,10 @@ hipError_t launch_mfma_fwd(const AttnParams& p, hipStream_t stream);
 bool mfma_fwd_is_qtiled(const AttnParams& p);
 // p.order points at tile_table_bytes(B, total_q) bytes (tile_map.h): prefix sums, then the example of every query tile
 hipError_t launch_mfma_fwd_qtiled(const AttnParams& p, hipStream_t stream);
+// Sliding window with a bounded, narrow window and many (sequence, head) items: one workgroup walks one item,
+// its waves rotate through the query blocks (attn_swa_band_mfma.hip).  p.order: sequences, longest first.
+bool swa_band_applies(const AttnParams& p);
+hipError_t launch_swa_band_fwd(const AttnParams& p, hipStream_t stream);
 bool mfma_bwd_supported(const AttnParams& p, int dtype);
 hipError_t launch_mfma_bwd(const AttnParams& p, void* workspace_tail, hipStream_t stream);
 size_t mfma_bwd_workspace_tail(int B, int H, int d, int max_q, int64_t total_q);
