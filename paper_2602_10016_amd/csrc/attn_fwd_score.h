@@ -32,6 +32,9 @@ __device__ __forceinline__ void score_to_weights(const f32x16& sacc, bool need_m
     for (int v = 0; v < 16; ++v) pv[v] = sacc[v];
     if (SOFTMAX) {
         if (need_mask) {
+            // (an empty volatile statement: the compiler must keep this a branch; folded into selects, the 48
+            // compare / select / add operations below would run for every tile, and few tiles need them)
+            asm volatile("");
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span;
@@ -63,6 +66,7 @@ __device__ __forceinline__ void score_to_weights(const f32x16& sacc, bool need_m
         }
         l_run += sum;
     } else if (need_mask) {
+        asm volatile("");  // a branch, as above
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const bool ok = rel0 + (unsigned)(8 * (v >> 2) + (v & 3)) <= key_span;

@@ -21,9 +21,9 @@
 // waves that drift apart by a tile or two overlap the matrix-core phase of one with the vector phase of
 // another on their SIMD.  Instead a compute wave waits (bounded polling of the LDS word) until its tile has
 // landed, and publishes its own progress - the first tile it may still read - in a word of its own; the loader
-// reuses a stage once every compute wave is past the tile it held.  Compute wave w owns query slot w: it loads
-// the query rows of its next block there itself (load-to-LDS, issued as soon as the previous block's output
-// rows have gone out through the same slot) and waits for them on its own counter.
+// reuses a stage once every compute wave is past the tile it held.  A compute wave fetches the query fragments
+// of its next block straight into registers during the last tile of the current one, and transposes its output
+// rows through an LDS slot of its own.
 //
 // Per tile and compute wave the arithmetic is that of the other forward kernels (S^T = K Q^T, online softmax
 // in registers, O^T += V^T P^T through transposing LDS reads).
@@ -38,7 +38,7 @@ struct BandSmem {
     static constexpr int TILE = KT * ROW;           // 32 rows of K, of V, or of a query block
     static constexpr int STAGE = 2 * TILE;          // K tile, then V tile
     static constexpr int R = 4;                     // ring stages
-    static constexpr int QSLOTS = R * STAGE;        // one slot per compute wave: its block's query rows, later its output rows
+    static constexpr int QSLOTS = R * STAGE;        // one slot per compute wave, for the transposition of its output rows
     static constexpr int FLAGS = QSLOTS + NWC * TILE;  // int32: [0] tiles landed, [1 + w] first tile compute wave w may still read
     static constexpr int TOTAL = FLAGS + 64;
     static_assert(TOTAL <= 160 * 1024, "one workgroup may use the whole LDS of a compute unit, not more");
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     const uint32_t row_bytes = (uint32_t)(hd * 2);
     const int64_t tile_bytes = (int64_t)KT * row_bytes;
     const uint32_t lds0 = lds_address(lds);
-    volatile int* const flags = (volatile int*)(lds + SM::FLAGS);
+    // (LDS address space kept in the type: a generic pointer would make every poll a flat memory operation)
+    volatile __attribute__((address_space(3))) int* const flags = (volatile __attribute__((address_space(3))) int*)(lds + SM::FLAGS);
 
     // the words start at "nothing landed, nothing read"; the only barrier of the kernel orders that before any wait
     if (tid <= NWC) flags[tid] = 0;
@@ -158,24 +159,18 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     unsigned key_span = 0u;
     int nq = 0;  // queries of the current block
 
-    // Query rows of block j -> this wave's slot (K-tile swizzle), asynchronously; counted by this wave's vmcnt.
-    // (The lane index passes through an empty volatile statement so that the address arithmetic of these rarely
-    // executed blocks is done in place and not kept in registers across the key loop.)
-    auto load_query_block = [&](int j) {
+    // B-operand fragments of block j straight from global memory into the registers that hold them (column = query
+    // r, contraction = channels 16*kc + 8g ..: lane (r, g) reads every second 16-byte chunk of its own query row;
+    // rows past the end repeat the last one).  Issued while the previous block's last tile and output are still
+    // in progress - the old fragments are dead after that tile's first contraction - so the round trip is hidden.
+    auto load_query_fragments = [&](int j) {
         int lane_w = lane;
-        asm volatile("" : "+v"(lane_w));
+        asm volatile("" : "+v"(lane_w));  // address arithmetic in place, not kept in registers across the key loop
         const int rows = n - KT * j < KT ? n - KT * j : KT;
-        const char* src = (const char*)((const bf16_t*)p.q + ((row0 + (int64_t)KT * j) * p.H + h) * D);
-        u32x4 rsrc = make_rsrc_words(src, (uint32_t)(rows - 1) * row_bytes + SM::ROW);
+        const int rq = (lane_w & 31) < rows ? (lane_w & 31) : rows - 1;
+        const bf16_t* src = (const bf16_t*)p.q + ((row0 + (int64_t)KT * j + rq) * p.H + h) * D + 8 * (lane_w >> 5);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) rsrc[i] = __builtin_amdgcn_readfirstlane(rsrc[i]);
-        const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_address(slot));
-#pragma unroll
-        for (int i = 0; i < QI; ++i) {
-            const int row = i * RPI + lane_w / CHUNKS;
-            const uint32_t rb = (uint32_t)(row < rows ? row : rows - 1) * row_bytes;  // rows past the end repeat the last one
-            load_to_lds_b128(rsrc, rb + (((lane_w % CHUNKS) ^ swizzle_of_row<D, SWZ_K>(row)) << 4), 0, dst + i * 1024);
-        }
+        for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(src + 16 * kc);
     };
     // lane holds query r, channels 32*db + 8*(v/4) + 4g + (v%4): transposed through the wave's slot (16-byte chunks
     // of a row XOR-swizzled by the row) and written as whole rows
@@ -209,17 +204,61 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the slot has been read, it may take the next query block
     };
 
+    // one key tile of the current block; LAST: the block's last tile - the next block's query fragments are requested
+    // as soon as this tile's first contraction has consumed the current ones
+    auto tile_step = [&](int jc, int s, bool last) {
+        // tile s has landed?  (lane 0 polls, the branch is uniform)
+        for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
+            const int landed = __builtin_amdgcn_readfirstlane(flags[0]);
+            if (landed > s) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        asm volatile("" ::: "memory");  // the tile reads below stay behind the poll
+        const char* st = lds + (s % SM::R) * SM::STAGE;
+        // ---- S^T = K Q^T
+        f32x16 sacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            const bf16x8 a = *(const bf16x8*)(st + (k_rd ^ (kc << 5)));
+            sacc = mfma32(a, qf[kc], sacc);
+        }
+        if (last && jc + NWC < NB) load_query_fragments(jc + NWC);
+        // ---- online softmax; only tiles that some query of the block sees partly take the masked path
+        const int key_base = s * KT;
+        const int tq_lo = KT * jc, tq_hi = KT * jc + nq - 1;
+        bool need_mask = key_base + KT > n || nq < KT;
+        if (key_base < tq_hi - p.left) need_mask = true;
+        if ((int64_t)key_base + KT - 1 > (int64_t)tq_lo + p.right) need_mask = true;
+        bf16x8 pf[2];
+        score_to_weights<KUNLUN_ACT_SOFTMAX, DB, 1>(sacc, need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref, l_run,
+                                                    oacc, 0, pf);
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const char* src = st + (v_rd ^ (db << 6)) + c * 16 * SM::ROW;
+                const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src));
+                const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * SM::ROW));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const bf16x8 a = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+                oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
+            }
+        }
+        // every LDS read of tile s has been issued (the LDS serves a wave's operations in order, and the empty
+        // statement keeps the compiler from moving the store up): publish
+        asm volatile("" ::: "memory");
+        if (lane == 0) flags[1 + cw] = s + 1;
+    };
+
     // this wave's blocks: cw, cw + NWC, ...
+    if (cw < NB) load_query_fragments(cw);
     for (int jc = cw; jc < NB; jc += NWC) {
         const int fj = plan.first(jc), ej = plan.last(jc);
         // from here on this wave reads no tile before fj
         if (lane == 0) flags[1 + cw] = fj;
-        load_query_block(jc);
-        wait_vmcnt<0>();  // (also the output rows of the previous block, which are older)
-        asm volatile("" ::: "memory");
-        // B-operand fragments (column = query r, contraction = channels 16*kc + 8g ..)
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(slot + (k_rd ^ (kc << 5)));  // = k_offset(r, 2 kc + g)
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -236,51 +275,8 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
             key_lo = empty ? 0x3fffffff : lo;
             key_span = empty ? 0u : (unsigned)(hi - lo);
         }
-        for (int s = fj; s <= ej; ++s) {
-            // tile s has landed?  (lane 0 polls, the branch is uniform)
-            for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
-                const int landed = __builtin_amdgcn_readfirstlane(flags[0]);
-                if (landed > s) break;
-                __builtin_amdgcn_s_sleep(1);
-            }
-            asm volatile("" ::: "memory");  // the tile reads below stay behind the poll
-            const char* st = lds + (s % SM::R) * SM::STAGE;
-            // ---- S^T = K Q^T
-            f32x16 sacc;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 a = *(const bf16x8*)(st + (k_rd ^ (kc << 5)));
-                sacc = mfma32(a, qf[kc], sacc);
-            }
-            // ---- online softmax; only tiles that some query of the block sees partly take the masked path
-            const int key_base = s * KT;
-            const int tq_lo = KT * jc, tq_hi = KT * jc + nq - 1;
-            bool need_mask = key_base + KT > n || nq < KT;
-            if (key_base < tq_hi - p.left) need_mask = true;
-            if ((int64_t)key_base + KT - 1 > (int64_t)tq_lo + p.right) need_mask = true;
-            bf16x8 pf[2];
-            score_to_weights<KUNLUN_ACT_SOFTMAX, DB, 1>(sacc, need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref,
-                                                        l_run, oacc, 0, pf);
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const char* src = st + (v_rd ^ (db << 6)) + c * 16 * SM::ROW;
-                    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src));
-                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * SM::ROW));
-                    typedef __attribute__((ext_vector_type(8))) short s16x8;
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
-                    oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
-                }
-            }
-            // every LDS read of tile s has been issued (the LDS serves a wave's operations in order, and the empty
-            // statement keeps the compiler from moving the store up): publish
-            asm volatile("" ::: "memory");
-            if (lane == 0) flags[1 + cw] = s + 1;
-        }
+        for (int s = fj; s < ej; ++s) tile_step(jc, s, false);
+        tile_step(jc, ej, true);
         write_block(jc);
     }
     // no further block: this wave holds back no stage
