@@ -13,7 +13,7 @@
 // App. "GDPA and Fused PFFN Kernel" (work of consecutive outer iterations overlapped because the inner loops
 // are short), arranged for 64-wide waves that share one compute unit's LDS.
 //
-// Wave 0 is the loader (it computes nothing): it sends key / value tiles ahead into a ring of four LDS stages by
+// Wave 0 is the loader (it computes nothing): it sends key / value tiles ahead into a ring of LDS stages by
 // buffer-load-to-LDS (lds_ring.h), counts its own loads (they complete in issue order) and publishes the number
 // of tiles that have landed in an LDS word.  The waves of the workgroup do NOT meet at barriers in the key loop:
 // a barrier per step would put every wave into the same phase at the same time (all on the matrix cores, then
@@ -22,8 +22,9 @@
 // another on their SIMD.  Instead a compute wave waits (bounded polling of the LDS word) until its tile has
 // landed, and publishes its own progress - the first tile it may still read - in a word of its own; the loader
 // reuses a stage once every compute wave is past the tile it held.  A compute wave fetches the query fragments
-// of its next block straight into registers during the last tile of the current one, and transposes its output
-// rows through an LDS slot of its own.
+// of its next block straight into registers during the last tile of the current one and transposes its output
+// rows through a small LDS slot of its own, so nearly the whole LDS is ring: seven stages, three tiles in
+// flight, the waves free to spread over the rest.
 //
 // Per tile and compute wave the arithmetic is that of the other forward kernels (S^T = K Q^T, online softmax
 // in registers, O^T += V^T P^T through transposing LDS reads).
@@ -35,11 +36,13 @@ namespace kunlun {
 template <int D, int NWC>
 struct BandSmem {
     static constexpr int ROW = D * 2;
-    static constexpr int TILE = KT * ROW;           // 32 rows of K, of V, or of a query block
+    static constexpr int TILE = KT * ROW;           // 32 rows of K or of V
     static constexpr int STAGE = 2 * TILE;          // K tile, then V tile
-    static constexpr int R = 4;                     // ring stages
-    static constexpr int QSLOTS = R * STAGE;        // one slot per compute wave, for the transposition of its output rows
-    static constexpr int FLAGS = QSLOTS + NWC * TILE;  // int32: [0] tiles landed, [1 + w] first tile compute wave w may still read
+    static constexpr int R = 7;                     // ring stages: the tiles the waves are spread over, and those in flight
+    static constexpr int F = 3;                     // tiles in flight
+    static constexpr int SLOT = TILE / 2;           // per compute wave: 16 output rows on their way to memory
+    static constexpr int SLOTS = R * STAGE;
+    static constexpr int FLAGS = SLOTS + NWC * SLOT;  // int32: [0] tiles landed, [1 + w] first tile compute wave w may still read
     static constexpr int TOTAL = FLAGS + 64;
     static_assert(TOTAL <= 160 * 1024, "one workgroup may use the whole LDS of a compute unit, not more");
 };
@@ -67,11 +70,9 @@ template <int D, int NWC>
 __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnParams p) {
     using SM = BandSmem<D, NWC>;
     using L = TileLayout<D>;
-    constexpr int KC = D / 16, DB = D / 32, CHUNKS = D / 8;
+    constexpr int KC = D / 16, DB = D / 32;
     constexpr int TI = 2 * TileDma<D, 1, SWZ_K>::INSTR;  // load instructions of a key / value tile pair
-    constexpr int QI = TileDma<D, 1, SWZ_K>::INSTR;      // ... of a query block
-    constexpr int RPI = TileDma<D, 1, SWZ_K>::RPI;       // rows per load instruction
-    static_assert(2 * TI < 64 && SM::R >= 3, "two tiles in flight: their loads must fit the vmcnt counter, their stages the ring");
+    static_assert(SM::F == 3 && SM::F * TI < 64 && SM::R > SM::F, "tiles in flight: their loads must fit the vmcnt counter, their stages the ring");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     // ---- the work item: workgroup i runs on XCD i % 8; consecutive sequences go to consecutive XCDs and each XCD
@@ -111,16 +112,16 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
         kdma.init(lane, 0, row_bytes);
         vdma.init(lane, 0, row_bytes);
         for (int t = 0; t < NT; ++t) {
-            // tiles t - 2 and t - 1 are in flight: once t - 2 has landed it is published, before anything else, so
-            // that waves ahead of the others are not held up by the wait below
-            if (t >= 2) {
-                wait_vmcnt<TI>();
+            // tiles t - F .. t - 1 are in flight: once t - F has landed it is published, before anything else, so that
+            // waves ahead of the others are not held up by the wait below
+            if (t >= SM::F) {
+                wait_vmcnt<(SM::F - 1) * TI>();
                 asm volatile("" ::: "memory");
-                if (lane == 0) flags[0] = t - 1;
+                if (lane == 0) flags[0] = t - SM::F + 1;
             }
             if (t >= SM::R) {
                 // the stage of tile t - R: every compute wave must be past that tile.  (It will be: a wave that is not
-                // has its tile in LDS already - tiles up to t - 2 have been published - and needs nothing from here.)
+                // has its tile in LDS already - tiles up to t - F have been published, F < R - and needs nothing from here.)
                 const int need = t - SM::R + 1;
                 for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
                     const int prog = lane < NWC ? flags[1 + lane] : need;
@@ -133,11 +134,9 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
             kdma.issue(K + t * tile_bytes, n - t * KT, dst);
             vdma.issue(V + t * tile_bytes, n - t * KT, dst + SM::TILE);
         }
-        if (NT >= 2) {
-            wait_vmcnt<TI>();
-            asm volatile("" ::: "memory");
-            if (lane == 0) flags[0] = NT - 1;
-        }
+        // the last tiles land one by one
+        if (NT >= 3) { wait_vmcnt<2 * TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = NT - 2; }
+        if (NT >= 2) { wait_vmcnt<TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = NT - 1; }
         wait_vmcnt<0>();
         asm volatile("" ::: "memory");
         if (lane == 0) flags[0] = NT;
@@ -150,7 +149,6 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     const float sc = p.scale * LOG2E;
     const int k_rd = L::k_offset(r, g);
     const int v_rd = SM::TILE + L::v_offset(4 * g + ((lane & 15) >> 2), (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
-    char* const slot = lds + SM::QSLOTS + cw * SM::TILE;
 
     bf16x8 qf[KC];
     f32x16 oacc[DB][1];
@@ -172,38 +170,46 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(src + 16 * kc);
     };
-    // lane holds query r, channels 32*db + 8*(v/4) + 4g + (v%4): transposed through the wave's slot (16-byte chunks
-    // of a row XOR-swizzled by the row) and written as whole rows
+    // Output rows of block j.  The lane holds query r, channels 32*db + 8*(v/4) + 4g + (v%4); the rows go out whole
+    // (16 lanes x 16 bytes each), 16 rows at a time through the wave's LDS slot (16-byte chunks of a row XOR-swizzled
+    // by the row).  (Stores of 32-byte pieces straight from registers were measured: 2.1 ms against 2.0 ms at the
+    // bench size, and 2.9 ms with the non-temporal hint.)
     auto write_block = [&](int j) {
         int lane_w = lane;
-        asm volatile("" : "+v"(lane_w));
+        asm volatile("" : "+v"(lane_w));  // address arithmetic in place, not kept in registers across the key loop
         const int r = lane_w & 31, g = lane_w >> 5;
+        constexpr int CHUNKS = D / 8;
+        char* const slot = lds + SM::SLOTS + cw * SM::SLOT;
         const float l_tot = halves_sum(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         const int64_t grow = row0 + (int64_t)KT * j;  // first row of the block in the packed tensors
         if (p.lse && g == 0 && r < nq)
             p.lse[(int64_t)h * p.total_q + grow + r] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                bf16x4 out;
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) out[e4] = (bf16_t)(oacc[db][0][4 * vg + e4] * inv);
-                *(bf16x4*)(slot + r * SM::ROW + (((4 * db + vg) ^ (r & (CHUNKS - 1))) << 4) + 8 * g) = out;
-            }
         bf16_t* obase = (bf16_t*)p.o + grow * hd + (int64_t)h * D;
-        constexpr int O_STORES = 32 * CHUNKS / 64;
+        constexpr int O_STORES = 16 * CHUNKS / 64;
         const int chunk = lane_w % CHUNKS, rsub = lane_w / CHUNKS;
 #pragma unroll
-        for (int i = 0; i < O_STORES; ++i) {
-            const int row = i * (64 / CHUNKS) + rsub;
-            const u32x4 val = *(const u32x4*)(slot + row * SM::ROW + ((chunk ^ (row & (CHUNKS - 1))) << 4));
-            if (row < nq) __builtin_nontemporal_store(val, (u32x4*)(obase + row * hd + chunk * 8));
+        for (int half = 0; half < 2; ++half) {
+            if ((r >> 4) == half) {
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int vg = 0; vg < 4; ++vg) {
+                        bf16x4 out;
+#pragma unroll
+                        for (int e4 = 0; e4 < 4; ++e4) out[e4] = (bf16_t)(oacc[db][0][4 * vg + e4] * inv);
+                        *(bf16x4*)(slot + (r & 15) * SM::ROW + (((4 * db + vg) ^ (r & (CHUNKS - 1))) << 4) + 8 * g) = out;
+                    }
+            }
+#pragma unroll
+            for (int i = 0; i < O_STORES; ++i) {
+                const int row = i * (64 / CHUNKS) + rsub;  // inside the half
+                const u32x4 val = *(const u32x4*)(slot + row * SM::ROW + ((chunk ^ (row & (CHUNKS - 1))) << 4));
+                if (16 * half + row < nq) __builtin_nontemporal_store(val, (u32x4*)(obase + (16 * half + row) * hd + chunk * 8));
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the slot has been read before the other half overwrites it
         }
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the slot has been read, it may take the next query block
     };
-
     // one key tile of the current block; LAST: the block's last tile - the next block's query fragments are requested
     // as soon as this tile's first contraction has consumed the current ones
     auto tile_step = [&](int jc, int s, bool last) {
