@@ -1,5 +1,5 @@
 """Sliding-window forward on the launches that take the one-workgroup-per-(sequence, head) kernel (bounded
-window of 8 to 11 block-steps, at least 2048 (sequence, head) items): full compare with the CPU oracle on ragged
+window of 8 to 11 block-steps, at least 512 (sequence, head) items): full compare with the CPU oracle on ragged
 batches, every supported head dimension, windows on both sides of the conditions, and bit-identity of the
 examples' results when other examples change."""
 import math
@@ -54,6 +54,12 @@ def test_band_windows_d128(kb, oracle, window):
 @pytest.mark.parametrize("window", [(255, 0), (96, 130)])
 def test_band_head_dimensions(kb, oracle, d, H, window):
     check(kb, oracle, 2048 // H + 8, H, d, 400, window, seed=d + window[0])
+
+
+@pytest.mark.parametrize("B,H", [(127, 4), (128, 4), (256, 2), (511, 1), (512, 1)])
+def test_band_item_count_threshold(kb, oracle, B, H):
+    """511 and 508 items take the query-tiled kernel, 512 the one-workgroup-per-item kernel."""
+    check(kb, oracle, B, H, 128, 600, (255, 0), seed=B * H)
 
 
 def test_band_many_short_sequences_and_empty_ones(kb, oracle):
