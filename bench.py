@@ -38,7 +38,7 @@ ORACLE_SAMPLE_EXAMPLES = 256
 # profiles/bench_cfg4_hbm_traffic.txt.  Valid for the default workload and seed only.  (The
 # counters sit between L2 and the memory fabric: re-reads that the 256 MB Infinity Cache serves
 # are included, which is what the sliding-window figure above its algorithmic 9.38 GB shows.)
-MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957134000, "gdpa_bwd": 9780146000, "swa_fwd": 10310206000}
+MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957134000, "gdpa_bwd": 9780146000, "swa_fwd": 9376853000}
 
 
 def device_normal(torch, shape, sigma, seed):
@@ -316,9 +316,16 @@ def main():
         ga = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
         gb = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
         tg, _ = timed(lambda: torch.matmul(ga, gb), n=10)
-        other["device_calibration"] = {"read_only_sum_1GiB_gbps": round((1 << 30) / tr / 1e3, 1),
-                                       "copy_1GiB_gbps_read_plus_write": round(2 * (1 << 30) / tw / 1e3, 1),
-                                       "three_reads_one_write_1GiB_operands_gbps": round(4 * (1 << 30) / t31 / 1e3, 1),
+        # the same three mixes by the library's own plain streaming kernel (kunlun_stream_probe: 16 KB per
+        # workgroup and stream, non-temporal), the best of the access patterns tried on this device
+        probe = {}
+        for name, reads, write in (("read_only", 3, 0), ("one_read_one_write", 1, 1), ("three_reads_one_write", 3, 1)):
+            tp, _ = timed(lambda: kb.stream_probe(src, flush, fc.view(torch.uint8), fd.view(torch.uint8), reads, write), n=10)
+            probe[name + "_gbps"] = round((reads + write) * (1 << 30) / tp / 1e3, 1)
+        other["device_calibration"] = {"stream_probe_1GiB_operands": probe,
+                                       "torch_sum_1GiB_gbps": round((1 << 30) / tr / 1e3, 1),
+                                       "torch_copy_1GiB_gbps_read_plus_write": round(2 * (1 << 30) / tw / 1e3, 1),
+                                       "torch_addcmul_three_reads_one_write_gbps": round(4 * (1 << 30) / t31 / 1e3, 1),
                                        "bf16_gemm_8192_tflops": round(2 * 8192 ** 3 / tg / 1e6, 1)}
         del src, ga, gb, flush, fa, fb, fc, fd
 

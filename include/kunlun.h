@@ -262,6 +262,17 @@ size_t kunlun_sumkron_bwd_workspace_bytes(int B, int S, int T, int D, int k, int
  */
 int kunlun_check_offsets(const int32_t* offsets, int B, int64_t total, int max_len, int32_t* violations, void* stream);
 
+/*
+ * Measurement aid, no part of any operator: one plain streaming kernel with the read : write mix of an attention
+ * call, to calibrate what the device's memory system sustains for that mix (the HBM roof the calls' achieved GB/s are
+ * held against: reads only for the forward over a long history, 1 : 1 for the backward, 3 : 1 for the sliding
+ * window).  Reads `reads` (1..3) of the device buffers a, b, c (`bytes` each, a multiple of 16; unused ones may be
+ * NULL) and, with write = 1, writes their XOR to out (device, `bytes`); with write = 0 nothing is written, but out
+ * must still be a device buffer of at least 4 KiB.  Traffic of a call: (reads + write) * bytes.  Enqueued on
+ * `stream`; errors as for the other entry points.
+ */
+int kunlun_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write, void* stream);
+
 /* Static, human-readable text for a kunlun_status. */
 const char* kunlun_strerror(int status);
 

@@ -23,7 +23,7 @@ ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD, OP_SEED_FWD, OP_SEED_BWD = 0, 1, 2, 3, 4, 5
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_seed_attn_fwd", "kunlun_seed_attn_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
-           "kunlun_check_offsets", "kunlun_strerror"]
+           "kunlun_check_offsets", "kunlun_stream_probe", "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -57,6 +57,8 @@ _lib.kunlun_sumkron_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i]
 _lib.kunlun_sumkron_bwd_workspace_bytes.restype = _sz
 _lib.kunlun_check_offsets.argtypes = [_vp, _i, _i64, _i, _vp, _vp]
 _lib.kunlun_check_offsets.restype = _i
+_lib.kunlun_stream_probe.argtypes = [_vp, _vp, _vp, _vp, _sz, _i, _i, _vp]
+_lib.kunlun_stream_probe.restype = _i
 _lib.kunlun_strerror.argtypes = [_i]
 _lib.kunlun_strerror.restype = ctypes.c_char_p
 
@@ -398,6 +400,21 @@ def sumkron_bwd(x, z, w, dy, *, workspace=None, stream=None):
     if rc != OK:
         raise KunlunError(rc)
     return dx, dz, dw
+
+
+def stream_probe(a, b, c, out, reads, write, *, stream=None):
+    """kunlun_stream_probe: one streaming pass over `reads` of the uint8 device buffers a, b, c (+ a write of out)."""
+    for name, t in (("a", a), ("b", b), ("c", c), ("out", out)):
+        _check(name, t, dtype=torch.uint8, optional=name in ("b", "c"))
+    for name, t in (("b", b), ("c", c)):
+        if t is not None and t.numel() != a.numel():
+            raise ValueError(f"{name}: {t.numel()} bytes, expected {a.numel()}")
+    if out.numel() < (a.numel() if write else 4096):
+        raise ValueError(f"out: {out.numel()} bytes are too few")
+    _on_device(a=a, b=b, c=c, out=out)
+    rc = _lib.kunlun_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(out), a.numel(), int(reads), int(write), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
 
 
 def check_offsets(offsets, total, max_len, *, stream=None) -> int:

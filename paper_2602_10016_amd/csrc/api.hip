@@ -121,6 +121,17 @@ int kunlun_check_offsets(const int32_t* offsets, int B, int64_t total, int max_l
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 
+int kunlun_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write, void* stream) {
+    if (reads < 1 || reads > 3 || (write != 0 && write != 1)) return KUNLUN_ERR_UNSUPPORTED;
+    if (bytes % 16 != 0) return KUNLUN_ERR_SHAPE;
+    if (bytes == 0) return KUNLUN_OK;
+    if (!a || (reads > 1 && !b) || (reads > 2 && !c) || !out) return KUNLUN_ERR_NULL;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16) || !aligned(out, 16)) return KUNLUN_ERR_ALIGN;
+    if (!write && bytes < 4096) return KUNLUN_ERR_SHAPE;  // `out` must hold 4 KiB even when nothing is written
+    const hipError_t e = launch_stream_probe(a, b, c, out, bytes, reads, write, (hipStream_t)stream);
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
 const char* kunlun_strerror(int status) {
     switch (status) {
     case KUNLUN_OK: return "ok";

@@ -55,6 +55,9 @@ hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int
 
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
 hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+hipError_t launch_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write,
+                               hipStream_t stream);
 hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int max_len, int32_t* violations, hipStream_t stream);
 // True when the launch is so small that every workgroup is resident at once (wgs_per_cu = how
 // many workgroups of the kernel fit one compute unit): the issue order then has no effect and
