@@ -205,7 +205,8 @@ int kunlun::gdpa_fwd_checked(const void* q, const void* k, const void* v, void* 
             p.order = nullptr;
         } else {
             p.order = order;
-            e = launch_schedule(kv_offsets, B, max_kv, order, s);
+            p.queue = (int32_t*)workspace;
+            e = launch_schedule(kv_offsets, B, max_kv, order, p.queue, s);
             if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
         }
         e = launch_mfma_fwd(p, s);
@@ -288,7 +289,8 @@ int gdpa_bwd_checked(const void* q, const void* k, const void* v, const void* o,
             p.order = nullptr;
         } else {
             p.order = order;
-            e = launch_schedule(kv_offsets, B, max_kv, order, s);
+            p.queue = (int32_t*)workspace;
+            e = launch_schedule(kv_offsets, B, max_kv, order, p.queue, s);
             if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
         }
         e = launch_mfma_bwd(p, (char*)workspace + WS_HEADER_BYTES + order_bytes(B), s);
@@ -335,7 +337,8 @@ int kunlun_swa_fwd(const void* q, const void* k, const void* v, void* o, float* 
     hipError_t e;
     if (mfma_fwd_supported(p, dtype) && swa_band_applies(p)) {
         int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);  // sequences, longest first
-        e = launch_schedule(offsets, B, max_len, order, s);
+        p.queue = (int32_t*)workspace;
+        e = launch_schedule(offsets, B, max_len, order, p.queue, s);
         if (e != hipSuccess) return KUNLUN_ERR_LAUNCH;
         p.order = order;
         e = launch_swa_band_fwd(p, s);

@@ -47,8 +47,11 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
     using SM = PairSmem;
     constexpr bool SOFTMAX = ACT == KUNLUN_ACT_SOFTMAX;
     constexpr int KC = D / 16;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    // (the thread index goes through an opaque move per item: everything derived from it is then computed where the
+    // item uses it, instead of being kept in registers across the persistent loop for all six score functions)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (scalar: the tile descriptors below depend on it)
     const int pair = wave >> 1, w = wave & 1;     // w: query block owned in the score phase, channel half in the dK/dV phase
     const int ptid = tid & 127;                   // thread index inside the pair
     const int r = lane & 31, g = lane >> 5;
@@ -163,16 +166,16 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
         }
     };
     fetch(pair);
+    if (pair < n_tiles) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *(u32x4*)(ldsK + uw[i]) = kst[i];
+            *(u32x4*)(ldsV + uw[i]) = vst[i];
+        }
+    }
     for (int it = 0; it < n_iter; ++it) {
         const int kt = 2 * it + pair;
         const bool active = kt < n_tiles;
-        if (active) {  // each thread overwrites exactly the staging chunks it read itself: no barrier
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                *(u32x4*)(ldsK + uw[i]) = kst[i];
-                *(u32x4*)(ldsV + uw[i]) = vst[i];
-            }
-        }
         __syncthreads();  // (1) K/V tiles complete
         fetch(kt + 2);
         bf16x8 dsf[2];
@@ -269,10 +272,21 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
             const int out_bytes = (rows - 1) * (int)row_bytes + D * 2;
             const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc((void*)(DVg + key_base * (int64_t)row_bytes), 0, out_bytes, 0x00020000);
             const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc((void*)(DKg + key_base * (int64_t)row_bytes), 0, out_bytes, 0x00020000);
+            // Whole rows, 16 bytes per lane; rows past the history are dropped.  A thread stores exactly the staging
+            // chunks that it fills with the next K/V tile, so the tile goes into LDS right here, behind the read of
+            // the chunk (LDS serves a wave in order) and without a barrier.  The order matters for more than the
+            // barrier: a wait for the tile's loads also waits for every older memory operation, and at this point the
+            // next older ones are the stores of the previous round, long complete - whereas after this round's
+            // stores it would expose their whole write latency in every round.
+            const bool next = kt + 2 < n_tiles;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {  // whole rows, 16 bytes per lane; rows past the history are dropped
+            for (int i = 0; i < 4; ++i) {
                 const u32x4 dvv = *(const u32x4*)(ldsV + uw[i]);
                 const u32x4 dkv = *(const u32x4*)(ldsK + uw[i]);
+                if (next) {
+                    *(u32x4*)(ldsV + uw[i]) = vst[i];
+                    *(u32x4*)(ldsK + uw[i]) = kst[i];
+                }
                 __builtin_amdgcn_raw_buffer_store_b128(dvv, vr, goff, 8 * i * row_bytes, 2);
                 __builtin_amdgcn_raw_buffer_store_b128(dkv, kr, goff, 8 * i * row_bytes, 2);
             }
@@ -309,38 +323,56 @@ __device__ __forceinline__ void attn_bwd_pair_item(const AttnParams& p, char* sm
     }
 }
 
-// one workgroup per (example, head), examples in scheduler order (longest history first);
-// workgroup i runs on XCD i % 8 and each XCD walks through all heads of its examples.
-__global__ __launch_bounds__(256, 2) void gdpa_bwd_pair_kernel(AttnParams p) {
+// Work items = (example, head), examples in scheduler order (longest history first), all heads of eight examples
+// before the next eight.  With a work counter (p.queue; launches with more items than resident workgroups) the
+// launch is persistent: two workgroups per compute unit, each starts with the item of its index and then takes
+// the next unclaimed one - the same longest-first list scheduling as the hardware dispatcher performs on a grid
+// of one workgroup per item, without its cost: measured on the jagged benchmark batch, the dispatcher kept only
+// 60-90 % of the workgroup slots occupied once the items became short.  The counter is asked for the next item
+// while the current one starts, so its round trip is never waited for.
+__global__ __launch_bounds__(256, 2) void gdpa_bwd_pair_kernel(AttnParams p, int n_items) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     constexpr int D = 128;
-    const int xcd = blockIdx.x & 7;
-    const int64_t j = blockIdx.x >> 3;
-    const int h = (int)(j % p.H);
-    const int64_t e = (j / p.H) * 8 + xcd;
-    if (e >= p.B) return;
-    const int b = p.order ? p.order[e] : (int)e;
-    const int64_t q0 = q_begin(p, b);
-    const int nq = (int)(q_end(p, b) - q0);
-    const int64_t k0 = p.kv_off[b];
-    const int n_kv = p.kv_off[b + 1] - (int)k0;
-    if (nq <= 0) {  // no query sees these keys: their gradients are zero
-        const int64_t hd = (int64_t)p.H * D;
-        const u32x4 z = {0, 0, 0, 0};
-        for (int idx = threadIdx.x; idx < n_kv * (D / 8); idx += 256) {
-            const int row = idx / (D / 8), c8 = idx % (D / 8);
-            *(u32x4*)((bf16_t*)p.dk + (k0 + row) * hd + (int64_t)h * D + c8 * 8) = z;
-            *(u32x4*)((bf16_t*)p.dv + (k0 + row) * hd + (int64_t)h * D + c8 * 8) = z;
+    // hand-over word for the next item: the last word of the second pair's dS tile, dead between items
+    volatile int* const next_word = (volatile int*)(smem + PairSmem::TOTAL - 4);
+    int item = blockIdx.x;
+    while (item < n_items) {
+        int claimed = 0;
+        if (p.queue && threadIdx.x == 0) claimed = atomicAdd(p.queue, 1);
+        const int slot = item & 7;
+        const int64_t j = item >> 3;
+        const int h = (int)(j % p.H);
+        const int64_t e = (j / p.H) * 8 + slot;
+        if (e < p.B) {
+            const int b = p.order ? p.order[e] : (int)e;
+            const int64_t q0 = q_begin(p, b);
+            const int nq = (int)(q_end(p, b) - q0);
+            const int64_t k0 = p.kv_off[b];
+            const int n_kv = p.kv_off[b + 1] - (int)k0;
+            if (nq <= 0) {  // no query sees these keys: their gradients are zero
+                const int64_t hd = (int64_t)p.H * D;
+                const u32x4 z = {0, 0, 0, 0};
+                for (int idx = threadIdx.x; idx < n_kv * (D / 8); idx += 256) {
+                    const int row = idx / (D / 8), c8 = idx % (D / 8);
+                    *(u32x4*)((bf16_t*)p.dk + (k0 + row) * hd + (int64_t)h * D + c8 * 8) = z;
+                    *(u32x4*)((bf16_t*)p.dv + (k0 + row) * hd + (int64_t)h * D + c8 * 8) = z;
+                }
+            } else {
+                switch (p.head_act[h]) {
+                case KUNLUN_ACT_SOFTMAX: attn_bwd_pair_item<KUNLUN_ACT_SOFTMAX>(p, smem, h, q0, nq, k0, n_kv); break;
+                case KUNLUN_ACT_IDENTITY: attn_bwd_pair_item<KUNLUN_ACT_IDENTITY>(p, smem, h, q0, nq, k0, n_kv); break;
+                case KUNLUN_ACT_RELU: attn_bwd_pair_item<KUNLUN_ACT_RELU>(p, smem, h, q0, nq, k0, n_kv); break;
+                case KUNLUN_ACT_GELU: attn_bwd_pair_item<KUNLUN_ACT_GELU>(p, smem, h, q0, nq, k0, n_kv); break;
+                case KUNLUN_ACT_GELU_TANH: attn_bwd_pair_item<KUNLUN_ACT_GELU_TANH>(p, smem, h, q0, nq, k0, n_kv); break;
+                default: attn_bwd_pair_item<KUNLUN_ACT_SILU>(p, smem, h, q0, nq, k0, n_kv); break;
+                }
+            }
         }
-        return;
-    }
-    switch (p.head_act[h]) {
-    case KUNLUN_ACT_SOFTMAX: attn_bwd_pair_item<KUNLUN_ACT_SOFTMAX>(p, smem, h, q0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_IDENTITY: attn_bwd_pair_item<KUNLUN_ACT_IDENTITY>(p, smem, h, q0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_RELU: attn_bwd_pair_item<KUNLUN_ACT_RELU>(p, smem, h, q0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_GELU: attn_bwd_pair_item<KUNLUN_ACT_GELU>(p, smem, h, q0, nq, k0, n_kv); break;
-    case KUNLUN_ACT_GELU_TANH: attn_bwd_pair_item<KUNLUN_ACT_GELU_TANH>(p, smem, h, q0, nq, k0, n_kv); break;
-    default: attn_bwd_pair_item<KUNLUN_ACT_SILU>(p, smem, h, q0, nq, k0, n_kv); break;
+        if (!p.queue) break;
+        __syncthreads();  // the item's last LDS reads (dQ sums) are done
+        if (threadIdx.x == 0) *next_word = claimed + (int)gridDim.x;
+        __syncthreads();
+        item = __builtin_amdgcn_readfirstlane(*next_word);  // (next written in the first round of the next item, behind its barriers)
     }
 }
 
@@ -351,7 +383,10 @@ hipError_t launch_mfma_bwd_pair(const AttnParams& p, hipStream_t stream) {
     static const hipError_t raised =
         hipFuncSetAttribute((const void*)gdpa_bwd_pair_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (raised != hipSuccess) return raised;
-    hipLaunchKernelGGL(gdpa_bwd_pair_kernel, dim3((unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H)), dim3(256), bytes, stream, p);
+    const int64_t n_items = (((int64_t)p.B + 7) / 8) * 8 * p.H;
+    const int64_t resident = 2 * (int64_t)compute_units();
+    const unsigned grid = (unsigned)(p.queue && n_items > resident ? resident : n_items);
+    hipLaunchKernelGGL(gdpa_bwd_pair_kernel, dim3(grid), dim3(256), bytes, stream, p, (int)n_items);
     return hipGetLastError();
 }
 

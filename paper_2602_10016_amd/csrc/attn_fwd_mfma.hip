@@ -106,8 +106,12 @@ __device__ __forceinline__ void attn_fwd_item(const AttnParams& p, char* lds, in
     constexpr int KC = D / 16;  // contraction steps of S^T = K Q^T
     constexpr int DB = D / 32;  // 32-channel blocks of O^T
     constexpr int QW = 32 * NQB;  // queries per wave
-    const int split = KS > 1 ? __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6) : 0;  // this wave's turn in the key tiles
-    const int tid = KS > 1 ? (int)(threadIdx.x & 63) : (int)threadIdx.x;
+    // (the thread index goes through an opaque move per item: what is derived from it is computed where the item
+    // uses it, and not kept in registers across the loop of a persistent launch for all six score functions)
+    int tid_wg = threadIdx.x;
+    asm volatile("" : "+v"(tid_wg));
+    const int split = KS > 1 ? __builtin_amdgcn_readfirstlane(tid_wg >> 6) : 0;  // this wave's turn in the key tiles
+    const int tid = KS > 1 ? (tid_wg & 63) : tid_wg;
     constexpr int LDS_BYTES = SM::bytes(KS);  // of one query-owning group of waves
     char* const lds_all = lds;
     lds += split * LDS_BYTES;
@@ -369,32 +373,50 @@ __device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds
     }
 }
 
-// GDPA / cross attention: one workgroup per (example, query tile, head), examples in scheduler
-// order (longest history first).
+// GDPA / cross attention: work items = (example, query tile, head), examples in scheduler order (longest
+// history first).  Item i belongs to "lane" i % 8: consecutive entries (example, query tile) go to consecutive
+// lanes and each lane walks through all heads of its entries - on a grid of one workgroup per item, where
+// workgroup i runs on XCD i % 8, every L2 so sees all address residues modulo the token stride H*D*2 (one head
+// per XCD would use only a fraction of the L2 channels).
+// With a work counter (p.queue: launches with more items than resident workgroups) the launch is persistent:
+// as many workgroups as fit the device, each starts with the item of its index and then takes the next
+// unclaimed one, which is the dispatcher's longest-first list scheduling without its cost (measured on the
+// jagged benchmark batch: with cheap score functions the dispatcher kept a third of the workgroup slots empty).
+// The counter is asked for the next item while the current one starts.
 template <int D, int NQB, int NW, int OCC, int AHEAD, int KS>
-__global__ __launch_bounds__(64 * NW * KS, OCC) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles) {
+__global__ __launch_bounds__(64 * NW * KS, OCC) void gdpa_fwd_mfma_kernel(AttnParams p, int n_qtiles, int n_items) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];  // KS * FwdSmem<D>::bytes(KS) bytes
     constexpr int QT = 32 * NQB * NW;
-    // Workgroup i runs on XCD i % 8.  Consecutive entries (example, query tile) go to
-    // consecutive XCDs and each XCD walks through all heads of its entries, so that every L2
-    // sees all address residues modulo the token stride H*D*2 (one head per XCD would use
-    // only a fraction of the L2 channels).
+    // hand-over word for the next item: the last word of the tile buffers, dead between items
+    volatile int* const next_word = (volatile int*)(lds + KS * FwdSmem<D>::bytes(KS) - 4);
     const int64_t n_entries = (int64_t)p.B * n_qtiles;
-    const int xcd = blockIdx.x & 7;
-    const int64_t j = blockIdx.x >> 3;
-    const int h = (int)(j % p.H);
-    const int64_t e = (j / p.H) * 8 + xcd;
-    if (e >= n_entries) return;
-    const int qt = (int)(e % n_qtiles);
-    const int b = p.order ? p.order[e / n_qtiles] : (int)(e / n_qtiles);
-    const int64_t qb0 = q_begin(p, b);
-    const int64_t nq_all = q_end(p, b) - qb0;
-    const int64_t q_first = (int64_t)qt * QT;
-    if (q_first >= nq_all) return;
-    const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
-    const int64_t k0 = p.kv_off[b];
-    const int n_kv = p.kv_off[b + 1] - (int)k0;
-    attn_fwd_dispatch<D, NQB, NW, AHEAD, KS>(p, lds, p.head_act[h], h, qb0 + q_first, nq, k0, n_kv);
+    int item = blockIdx.x;
+    while (item < n_items) {
+        int claimed = 0;
+        if (KS == 1 && p.queue && threadIdx.x == 0) claimed = atomicAdd(p.queue, 1);
+        const int slot = item & 7;
+        const int64_t j = item >> 3;
+        const int h = (int)(j % p.H);
+        const int64_t e = (j / p.H) * 8 + slot;
+        if (e < n_entries) {
+            const int qt = (int)(e % n_qtiles);
+            const int b = p.order ? p.order[e / n_qtiles] : (int)(e / n_qtiles);
+            const int64_t qb0 = q_begin(p, b);
+            const int64_t nq_all = q_end(p, b) - qb0;
+            const int64_t q_first = (int64_t)qt * QT;
+            if (q_first < nq_all) {
+                const int nq = (int)((nq_all - q_first) < QT ? (nq_all - q_first) : QT);
+                const int64_t k0 = p.kv_off[b];
+                const int n_kv = p.kv_off[b + 1] - (int)k0;
+                attn_fwd_dispatch<D, NQB, NW, AHEAD, KS>(p, lds, p.head_act[h], h, qb0 + q_first, nq, k0, n_kv);
+            }
+        }
+        if (KS > 1 || !p.queue) break;
+        __syncthreads();  // the item's last LDS reads (output rows) are done
+        if (threadIdx.x == 0) *next_word = claimed + (int)gridDim.x;
+        __syncthreads();
+        item = __builtin_amdgcn_readfirstlane(*next_word);  // (next written by the second key tile of the next item, behind barriers)
+    }
 }
 
 bool mfma_fwd_supported(const AttnParams& p, int dtype) {
@@ -417,8 +439,19 @@ static hipError_t launch_gdpa(const AttnParams& p, hipStream_t stream) {
         if (raised != hipSuccess) return raised;
     }
     const int n_qtiles = (p.max_q + QT - 1) / QT;
-    const unsigned grid = (unsigned)((((int64_t)p.B * n_qtiles + 7) / 8) * 8 * p.H);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW * KS), bytes, stream, p, n_qtiles);
+    const int64_t n_items = (((int64_t)p.B * n_qtiles + 7) / 8) * 8 * p.H;
+    int64_t grid = n_items;
+    if (KS == 1 && p.queue) {
+        // workgroups of this kernel that fit the device (once per process, like the attribute above)
+        static const int per_cu = [&] {
+            int n = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)kern, 64 * NW * KS, bytes) != hipSuccess || n < 1) n = 1;
+            return n;
+        }();
+        const int64_t resident = (int64_t)per_cu * compute_units();
+        if (grid > resident) grid = resident;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * NW * KS), bytes, stream, p, n_qtiles, (int)n_items);
     return hipGetLastError();
 }
 

@@ -23,6 +23,7 @@ struct AttnParams {
     const int32_t* q_off;   // null: dense queries, max_q rows per example
     const int32_t* kv_off;
     const int32_t* order;   // examples, longest history first (written by the scheduler kernel); null: 0..B-1
+    int32_t* queue;         // work counter of a persistent launch (zeroed by the scheduler kernel); null: one item per workgroup
     int B, H, d, max_q, max_kv;
     int64_t total_q, total_kv;
     float scale;
@@ -54,7 +55,11 @@ inline size_t seed_grad_partial_bytes(int B, int64_t n_elems) {
 hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int B, int64_t n_elems, int dtype, hipStream_t stream);
 
 // ---- launchers (each enqueues on `stream`, returns the hipError_t of the launch) ----
-hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream);
+// Sorts the examples by length (longest first) into order[B] and zeroes the WS_HEADER_BYTES of work counters at
+// `counters` (the start of the workspace) for the persistent kernels that follow on the stream.
+hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, int32_t* counters, hipStream_t stream);
+// Compute units of the current device (cached per process).
+int compute_units();
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 hipError_t launch_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write,
                                hipStream_t stream);

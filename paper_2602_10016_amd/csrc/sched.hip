@@ -15,10 +15,12 @@ constexpr int NBINS = 2048;
 constexpr int SCHED_THREADS = 1024;
 
 __global__ __launch_bounds__(SCHED_THREADS) void schedule_kernel(const int32_t* __restrict__ kv_off, int B,
-                                                                  int max_kv, int32_t* __restrict__ order) {
+                                                                  int max_kv, int32_t* __restrict__ order,
+                                                                  int32_t* __restrict__ counters) {
     __shared__ int hist[NBINS];
     __shared__ int scan[NBINS];
     const int tid = threadIdx.x;
+    if (tid < (int)(WS_HEADER_BYTES / sizeof(int32_t))) counters[tid] = 0;
     for (int i = tid; i < NBINS; i += SCHED_THREADS) hist[i] = 0;
     __syncthreads();
     const int64_t span = (int64_t)max_kv + 1;
@@ -82,10 +84,20 @@ hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int ma
 // MI355X has 256 compute units.
 bool schedule_is_moot(int64_t workgroups, int wgs_per_cu) { return workgroups <= (int64_t)wgs_per_cu * 256; }
 
-hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, hipStream_t stream) {
+hipError_t launch_schedule(const int32_t* kv_off, int B, int max_kv, int32_t* order, int32_t* counters, hipStream_t stream) {
     if (B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, kv_off, B, max_kv, order);
+    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(SCHED_THREADS), 0, stream, kv_off, B, max_kv, order, counters);
     return hipGetLastError();
+}
+
+int compute_units() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;  // MI355X
+        return cus;
+    }();
+    return n;
 }
 
 }  // namespace kunlun
