@@ -165,6 +165,37 @@ def main():
                                   "(profiles/bench_cfg4_hbm_traffic.txt), not measured in this run",
                 "algorithmic_bytes": int(nbytes[dom])}
 
+    # What the memory system sustains for the ACCESS PATTERN of each call, measured now: the same tensors, offsets,
+    # issue order and persistent launch, one walk per (example, head) that only moves the bytes
+    # (kunlun_jagged_stream_probe; the Q / O / dQ rows, 3 % of the bytes, are left out).  Best of 1, 2 and 4
+    # workgroups per compute unit.  A flat sweep over contiguous buffers (device_calibration below) runs faster
+    # than any such walk: many independent walkers at unrelated places load the memory channels unevenly.
+    def probe_ms(fn, n=5):
+        fn()
+        a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a_.record()
+        for _ in range(n):
+            fn()
+        b_.record()
+        torch.cuda.synchronize()
+        return a_.elapsed_time(b_) / n
+
+    _, dk_, dv_ = grads["g"]
+    ws_p = torch.empty(256 + (4 * (B + 1) + 255) // 256 * 256, dtype=torch.uint8, device="cuda")
+    pattern = {}
+    for name, (pa, pb, pc, oa, ob, nr, nw) in {"gdpa_fwd": (k, v, None, None, None, 2, 0), "gdpa_bwd": (k, v, None, dk_, dv_, 2, 2),
+                                               "swa_fwd": (qs, k, v, o_swa, None, 3, 1)}.items():
+        best = min(probe_ms(lambda: kb.jagged_stream_probe(pa, pb, pc, oa, ob, off, max_kv, nr, nw, wg, workspace=ws_p))
+                   for wg in (1, 2, 4))
+        moved = (nr + nw) * T * H * d * 2
+        pattern[name] = {"probe_gbps": round(moved / best / 1e6, 1), "probe_ms": round(best, 4),
+                         "kernel_gbps": breakdown[name]["gbps"],
+                         "kernel_vs_probe": round(breakdown[name]["gbps"] / (moved / best / 1e6), 3)}
+    roofline["access_pattern_roof"] = {"unit": "GB/s", "achieved_by_byte_moving_probe": pattern[dom]["probe_gbps"],
+                                       "frac_of_probe": pattern[dom]["kernel_vs_probe"]}
+    del dk_, dv_
+
     # The other the benchmark spec workloads (parity-test cases, small): timed separately, no part of
     # `value`; reported for their achieved HBM GB/s.  Their inputs fit the 256 MB Infinity Cache, so
     # back-to-back launches are warm-cache figures: the primary numbers (us, gbps, tflops) are COLD
@@ -365,7 +396,8 @@ def main():
                                f"sigma 1) clipped [32,4096], T={T} tokens; step = gdpa_fwd(gelu, 1/tau) + gdpa_bwd + "
                                f"swa_fwd(window 256 causal) on the same batch; value = the two GDPA calls", "seed": args.seed,
                    "step_gflop": round(total_flops / 1e9, 1)},
-        "breakdown": breakdown, "roofline": roofline, "cpu_baseline": cpu_baseline, "other_configs": other,
+        "breakdown": breakdown, "roofline": roofline, "access_pattern_probe": pattern, "cpu_baseline": cpu_baseline,
+        "other_configs": other,
     }
     print(json.dumps(out))
 

@@ -273,6 +273,25 @@ int kunlun_check_offsets(const int32_t* offsets, int B, int64_t total, int max_l
  */
 int kunlun_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write, void* stream);
 
+/*
+ * The same aid for the access pattern of the jagged attention calls, whose memory traffic is not one sweep over
+ * contiguous buffers but one independent walk per (example, head): work items in the scheduler's order (longest
+ * first) on a persistent launch of workgroups_per_cu (1..8) workgroups per compute unit, as in the attention
+ * kernels; a workgroup walks the token rows of its item and moves, per row, the d-channel piece of its head.
+ * a, b, c, out_a, out_b: device, bf16 [total, H, d] (d in {32, 64, 128}), 16-byte aligned; offsets: device int32
+ * [B + 1] as for the attention calls (lengths <= max_len, offsets[B] = total).  reads (1..3) of a, b, c are read;
+ * with x = a and y = b ^ c (of what is read; bitwise), writes = 0 stores nothing, writes = 1 stores x ^ y to
+ * out_a, writes = 2 (needs reads >= 2) stores x to out_a and y to out_b; unused pointers may be NULL.  Rows and
+ * heads outside the items are never touched.  Traffic of a call: (reads + writes) * total * H * d * 2 bytes.
+ * workspace: device, 256-byte aligned, at least 256 + 4 * (B + 1) rounded up to a multiple of 256 bytes (issue
+ * order and work counter; contents undefined afterwards).  Enqueued on `stream`; errors as for the other entry
+ * points.  Read-only forward over a history: reads = 2; its backward (K, V in, dK, dV out): reads = 2,
+ * writes = 2; sliding-window forward (Q, K, V in, O out): reads = 3, writes = 1.
+ */
+int kunlun_jagged_stream_probe(const void* a, const void* b, const void* c, void* out_a, void* out_b, const int32_t* offsets,
+                               int B, int H, int d, int max_len, int64_t total, int reads, int writes, int workgroups_per_cu,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Static, human-readable text for a kunlun_status. */
 const char* kunlun_strerror(int status);
 

@@ -23,7 +23,7 @@ ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD, OP_SEED_FWD, OP_SEED_BWD = 0, 1, 2, 3, 4, 5
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_seed_attn_fwd", "kunlun_seed_attn_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",
-           "kunlun_check_offsets", "kunlun_stream_probe", "kunlun_strerror"]
+           "kunlun_check_offsets", "kunlun_stream_probe", "kunlun_jagged_stream_probe", "kunlun_strerror"]
 
 _vp, _i, _i64, _f, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _lib.kunlun_gdpa_fwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i64, _i64, _f, _i, _vp, _i,
@@ -59,6 +59,8 @@ _lib.kunlun_check_offsets.argtypes = [_vp, _i, _i64, _i, _vp, _vp]
 _lib.kunlun_check_offsets.restype = _i
 _lib.kunlun_stream_probe.argtypes = [_vp, _vp, _vp, _vp, _sz, _i, _i, _vp]
 _lib.kunlun_stream_probe.restype = _i
+_lib.kunlun_jagged_stream_probe.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i64, _i, _i, _i, _vp, _sz, _vp]
+_lib.kunlun_jagged_stream_probe.restype = _i
 _lib.kunlun_strerror.argtypes = [_i]
 _lib.kunlun_strerror.restype = ctypes.c_char_p
 
@@ -413,6 +415,29 @@ def stream_probe(a, b, c, out, reads, write, *, stream=None):
         raise ValueError(f"out: {out.numel()} bytes are too few")
     _on_device(a=a, b=b, c=c, out=out)
     rc = _lib.kunlun_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(out), a.numel(), int(reads), int(write), _stream(stream))
+    if rc != OK:
+        raise KunlunError(rc)
+
+
+def jagged_stream_probe(a, b, c, out_a, out_b, offsets, max_len, reads, writes, workgroups_per_cu, *, workspace=None,
+                        stream=None):
+    """kunlun_jagged_stream_probe: one walk per (example, head) over the rows of bf16 [total, H, d] tensors."""
+    _check("a", a, dtype=torch.bfloat16)
+    if a.dim() != 3:
+        raise ValueError(f"a: expected [total, H, d], got shape {tuple(a.shape)}")
+    for name, t in (("b", b), ("c", c), ("out_a", out_a), ("out_b", out_b)):
+        _check(name, t, dtype=torch.bfloat16, shape=a.shape, optional=True)
+    total, H, d = a.shape
+    _check_offsets("offsets", offsets)
+    B = offsets.numel() - 1
+    need = 256 + (4 * (B + 1) + 255) // 256 * 256
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=a.device)
+    _check("workspace", workspace, dtype=torch.uint8)
+    _on_device(a=a, b=b, c=c, out_a=out_a, out_b=out_b, offsets=offsets, workspace=workspace)
+    rc = _lib.kunlun_jagged_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(out_a), _ptr(out_b), _ptr(offsets), B, H, d, int(max_len),
+                                         total, int(reads), int(writes), int(workgroups_per_cu), _ptr(workspace),
+                                         workspace.numel(), _stream(stream))
     if rc != OK:
         raise KunlunError(rc)
 

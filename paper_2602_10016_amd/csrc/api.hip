@@ -132,6 +132,27 @@ int kunlun_stream_probe(const void* a, const void* b, const void* c, void* out, 
     return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
 }
 
+int kunlun_jagged_stream_probe(const void* a, const void* b, const void* c, void* out_a, void* out_b, const int32_t* offsets,
+                               int B, int H, int d, int max_len, int64_t total, int reads, int writes, int workgroups_per_cu,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    if (B < 0 || H < 1 || H > KUNLUN_MAX_HEADS || max_len < 0 || total < 0) return KUNLUN_ERR_SHAPE;
+    if (d != 32 && d != 64 && d != 128) return KUNLUN_ERR_UNSUPPORTED;
+    if (reads < 1 || reads > 3 || writes < 0 || writes > 2 || (writes == 2 && reads < 2)) return KUNLUN_ERR_UNSUPPORTED;
+    if (workgroups_per_cu < 1 || workgroups_per_cu > 8) return KUNLUN_ERR_UNSUPPORTED;
+    if ((size_t)total * H * d * 2 > ((size_t)1 << 40)) return KUNLUN_ERR_SHAPE;
+    if (B == 0 || total == 0) return KUNLUN_OK;
+    if (!offsets || !a || (reads > 1 && !b) || (reads > 2 && !c) || (writes > 0 && !out_a) || (writes > 1 && !out_b)) return KUNLUN_ERR_NULL;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16) || !aligned(out_a, 16) || !aligned(out_b, 16)) return KUNLUN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < WS_HEADER_BYTES + order_bytes(B)) return KUNLUN_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return KUNLUN_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* queue = (int32_t*)workspace;
+    int32_t* order = (int32_t*)((char*)workspace + WS_HEADER_BYTES);
+    hipError_t e = launch_schedule(offsets, B, max_len, order, queue, s);
+    if (e == hipSuccess) e = launch_jagged_probe(a, b, c, out_a, out_b, order, offsets, B, H, d, queue, reads, writes, workgroups_per_cu, s);
+    return e == hipSuccess ? KUNLUN_OK : KUNLUN_ERR_LAUNCH;
+}
+
 const char* kunlun_strerror(int status) {
     switch (status) {
     case KUNLUN_OK: return "ok";

@@ -63,6 +63,11 @@ int compute_units();
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 hipError_t launch_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write,
                                hipStream_t stream);
+// x = a, y = b ^ c over the d-channel pieces of every (example, head) item (bf16 rows of H * d channels), items in
+// `order`, handed out by `queue`; writes: 0 none, 1 out_a = x ^ y, 2 out_a = x and out_b = y (writes = 2 needs reads >= 2)
+hipError_t launch_jagged_probe(const void* a, const void* b, const void* c, void* out_a, void* out_b, const int32_t* order,
+                               const int32_t* off, int B, int H, int d, int32_t* queue, int reads, int writes, int wgs_per_cu,
+                               hipStream_t stream);
 hipError_t launch_check_offsets(const int32_t* off, int B, int64_t total, int max_len, int32_t* violations, hipStream_t stream);
 // True when the launch is so small that every workgroup is resident at once (wgs_per_cu = how
 // many workgroups of the kernel fit one compute unit): the issue order then has no effect and

@@ -143,56 +143,3 @@ hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int
 }
 
 }  // namespace kunlun
-
-namespace kunlun {
-
-// ---- streaming probe: what this memory system sustains for a given read : write mix (calibration of the HBM
-// roof that the attention calls are held against).  Block b handles the 16 KB segment b of every stream: `reads`
-// (1..3) streams are read with non-temporal loads and combined, the result is written to `out` when `write` is
-// set, else folded into a value that is never stored.  The fastest of the access patterns tried on this device.
-template <int NR, bool WRITE>
-__global__ __launch_bounds__(256) void stream_probe_kernel(const u32x4_t* __restrict__ a, const u32x4_t* __restrict__ b,
-                                                           const u32x4_t* __restrict__ c, u32x4_t* __restrict__ out, size_t n16) {
-    const size_t s0 = (size_t)blockIdx.x * 1024;
-    u32x4_t acc = {0, 0, 0, 0};
-    u32x4_t v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const size_t j = s0 + u * 256 + threadIdx.x;
-        if (j < n16) {
-            v[u] = __builtin_nontemporal_load(a + j);
-            if (NR > 1) v[u] ^= __builtin_nontemporal_load(b + j);
-            if (NR > 2) v[u] ^= __builtin_nontemporal_load(c + j);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const size_t j = s0 + u * 256 + threadIdx.x;
-        if (j < n16) {
-            if (WRITE) __builtin_nontemporal_store(v[u], out + j);
-            else acc ^= v[u];
-        }
-    }
-    if (!WRITE && acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u) out[threadIdx.x] = acc;  // (keeps the loads alive)
-}
-
-hipError_t launch_stream_probe(const void* a, const void* b, const void* c, void* out, size_t bytes, int reads, int write,
-                               hipStream_t stream) {
-    const size_t n16 = bytes / 16;
-    if (n16 == 0) return hipSuccess;
-    const dim3 grid((unsigned)((n16 + 1023) / 1024)), block(256);
-    const u32x4_t *pa = (const u32x4_t*)a, *pb = (const u32x4_t*)b, *pc = (const u32x4_t*)c;
-    u32x4_t* po = (u32x4_t*)out;
-    if (write) {
-        if (reads == 1) hipLaunchKernelGGL((stream_probe_kernel<1, true>), grid, block, 0, stream, pa, pb, pc, po, n16);
-        else if (reads == 2) hipLaunchKernelGGL((stream_probe_kernel<2, true>), grid, block, 0, stream, pa, pb, pc, po, n16);
-        else hipLaunchKernelGGL((stream_probe_kernel<3, true>), grid, block, 0, stream, pa, pb, pc, po, n16);
-    } else {
-        if (reads == 1) hipLaunchKernelGGL((stream_probe_kernel<1, false>), grid, block, 0, stream, pa, pb, pc, po, n16);
-        else if (reads == 2) hipLaunchKernelGGL((stream_probe_kernel<2, false>), grid, block, 0, stream, pa, pb, pc, po, n16);
-        else hipLaunchKernelGGL((stream_probe_kernel<3, false>), grid, block, 0, stream, pa, pb, pc, po, n16);
-    }
-    return hipGetLastError();
-}
-
-}  // namespace kunlun

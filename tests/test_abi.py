@@ -20,7 +20,7 @@ def kb():
 def test_exports_match_header(kb):
     header = open(os.path.join(ROOT, "include", "kunlun.h")).read()
     declared = set(re.findall(r"^(?:int|size_t|const char\*)\s+(kunlun_\w+)\(", header, flags=re.M))
-    assert len(declared) == 15
+    assert len(declared) == 16
     assert declared == set(kb.EXPORTS)
     lib = kb.raw()
     for name in declared:
