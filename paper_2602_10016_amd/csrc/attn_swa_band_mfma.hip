@@ -66,8 +66,15 @@ struct BandPlan {
 // guarantees that a mistake in that reasoning would show as wrong numbers and not as a wave that never exits.
 constexpr int BAND_SPIN_LIMIT = 1 << 16;
 
+// One (sequence, head) of the launch as a wave sees it (all fields wave-uniform).
+struct BandItem {
+    int64_t row0;  // first row of the sequence in the packed tensors
+    int n;         // its rows; <= 0: nothing to do (empty sequence, or padding of the item grid)
+    int h;
+};
+
 template <int D, int NWC>
-__global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnParams p) {
+__global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnParams p, int n_items) {
     using SM = BandSmem<D, NWC>;
     using L = TileLayout<D>;
     constexpr int KC = D / 16, DB = D / 32;
@@ -75,20 +82,33 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     static_assert(SM::F == 3 && SM::F * TI < 64 && SM::R > SM::F, "tiles in flight: their loads must fit the vmcnt counter, their stages the ring");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
-    // ---- the work item: workgroup i runs on XCD i % 8; consecutive sequences go to consecutive XCDs and each XCD
-    // walks all heads of its sequences (all L2 channels in use), sequences in scheduler order (longest first)
-    const int xcd = blockIdx.x & 7;
-    const int64_t jj = blockIdx.x >> 3;
-    const int h = (int)(jj % p.H);
-    const int64_t e = (jj / p.H) * 8 + xcd;
-    if (e >= p.B) return;
-    const int b = p.order ? p.order[e] : (int)e;
-    const int64_t row0 = p.kv_off[b];
-    const int n = p.kv_off[b + 1] - (int)row0;
-    if (n <= 0) return;
-    BandPlan plan;
-    plan.n = n; plan.left = p.left; plan.right = p.right; plan.n_tiles = (n + KT - 1) / KT;
-    const int NT = plan.n_tiles, NB = plan.n_tiles;  // key tiles, query blocks
+    // ---- the work items of this workgroup.  The launch is persistent (one workgroup per compute unit): workgroup w
+    // of G takes the items w, 2G - 1 - w, 2G + w, 4G - 1 - w, ... of the list (sequences in scheduler order, longest
+    // first; all heads of eight sequences, then the next eight) - on a list sorted by length the forward and the
+    // backward sweep of every pair of rounds add up to nearly the same work for every workgroup.  Every wave walks
+    // that list on its own with scalar loads, one item ahead, and the key tiles of ALL its items form one stream
+    // with one running tile number: the loader goes on into the next item while the compute waves finish the
+    // current one, so an item's first tiles are already in the ring when its first blocks start.
+    const int G = gridDim.x;
+    // (scalar loads: the lists are read-only for the whole kernel)
+    const __attribute__((address_space(4))) int32_t* const order_c = (const __attribute__((address_space(4))) int32_t*)(uintptr_t)p.order;
+    const __attribute__((address_space(4))) int32_t* const off_c = (const __attribute__((address_space(4))) int32_t*)(uintptr_t)p.kv_off;
+    auto describe = [&](int k, BandItem& it) -> bool {
+        const int64_t i = (int64_t)k * G + ((k & 1) ? G - 1 - (int)blockIdx.x : (int)blockIdx.x);
+        if (i >= n_items) return false;
+        const int slot = (int)(i & 7);
+        const int64_t jj = i >> 3;
+        it.h = (int)(jj % p.H);
+        const int64_t e = (jj / p.H) * 8 + slot;
+        it.row0 = 0;
+        it.n = 0;
+        if (e < p.B) {
+            const int b = order_c ? order_c[e] : (int)e;
+            it.row0 = off_c[b];
+            it.n = off_c[b + 1] - (int)it.row0;
+        }
+        return true;
+    };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -105,41 +125,54 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
 
     if (wave == 0) {
         // ================= loader =================
-        const char* K = (const char*)((const bf16_t*)p.k + (row0 * p.H + h) * D);
-        const char* V = (const char*)((const bf16_t*)p.v + (row0 * p.H + h) * D);
         TileDma<D, 1, SWZ_K> kdma;
         TileDma<D, 1, SWZ_V> vdma;
         kdma.init(lane, 0, row_bytes);
         vdma.init(lane, 0, row_bytes);
-        for (int t = 0; t < NT; ++t) {
-            // tiles t - F .. t - 1 are in flight: once t - F has landed it is published, before anything else, so that
-            // waves ahead of the others are not held up by the wait below
-            if (t >= SM::F) {
-                wait_vmcnt<(SM::F - 1) * TI>();
-                asm volatile("" ::: "memory");
-                if (lane == 0) flags[0] = t - SM::F + 1;
-            }
-            if (t >= SM::R) {
-                // the stage of tile t - R: every compute wave must be past that tile.  (It will be: a wave that is not
-                // has its tile in LDS already - tiles up to t - F have been published, F < R - and needs nothing from here.)
-                const int need = t - SM::R + 1;
-                for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
-                    const int prog = lane < NWC ? flags[1 + lane] : need;
-                    if (__builtin_amdgcn_ballot_w64(prog < need) == 0) break;
-                    __builtin_amdgcn_s_sleep(1);
+        int T = 0;  // running tile number over all items of this workgroup
+        BandItem cur, nxt;
+        bool have = describe(0, cur);
+        for (int k = 0; have; ++k) {
+            const bool have_nxt = describe(k + 1, nxt);
+            if (cur.n > 0) {
+                const int n = cur.n;
+                const int NT = (n + KT - 1) / KT;
+                const char* K = (const char*)((const bf16_t*)p.k + (cur.row0 * p.H + cur.h) * D);
+                const char* V = (const char*)((const bf16_t*)p.v + (cur.row0 * p.H + cur.h) * D);
+                for (int t = 0; t < NT; ++t, ++T) {
+                    // tiles T - F .. T - 1 are in flight: once T - F has landed it is published, before anything else, so
+                    // that waves ahead of the others are not held up by the wait below
+                    if (T >= SM::F) {
+                        wait_vmcnt<(SM::F - 1) * TI>();
+                        asm volatile("" ::: "memory");
+                        if (lane == 0) flags[0] = T - SM::F + 1;
+                    }
+                    if (T >= SM::R) {
+                        // the stage of tile T - R: every compute wave must be past that tile.  (It will be: a wave that is
+                        // not has its tile in LDS already - tiles up to T - F have been published, F < R - and needs
+                        // nothing from here.)
+                        const int need = T - SM::R + 1;
+                        for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
+                            const int prog = lane < NWC ? flags[1 + lane] : need;
+                            if (__builtin_amdgcn_ballot_w64(prog < need) == 0) break;
+                            __builtin_amdgcn_s_sleep(1);
+                        }
+                        asm volatile("" ::: "memory");  // the loads below stay behind the poll
+                    }
+                    const uint32_t dst = lds0 + (T % SM::R) * SM::STAGE;
+                    kdma.issue(K + t * tile_bytes, n - t * KT, dst);
+                    vdma.issue(V + t * tile_bytes, n - t * KT, dst + SM::TILE);
                 }
-                asm volatile("" ::: "memory");  // the loads below stay behind the poll
             }
-            const uint32_t dst = lds0 + (t % SM::R) * SM::STAGE;
-            kdma.issue(K + t * tile_bytes, n - t * KT, dst);
-            vdma.issue(V + t * tile_bytes, n - t * KT, dst + SM::TILE);
+            cur = nxt;
+            have = have_nxt;
         }
         // the last tiles land one by one
-        if (NT >= 3) { wait_vmcnt<2 * TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = NT - 2; }
-        if (NT >= 2) { wait_vmcnt<TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = NT - 1; }
+        if (T >= 3) { wait_vmcnt<2 * TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = T - 2; }
+        if (T >= 2) { wait_vmcnt<TI>(); asm volatile("" ::: "memory"); if (lane == 0) flags[0] = T - 1; }
         wait_vmcnt<0>();
         asm volatile("" ::: "memory");
-        if (lane == 0) flags[0] = NT;
+        if (lane == 0) flags[0] = T;
         return;
     }
 
@@ -157,16 +190,16 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     unsigned key_span = 0u;
     int nq = 0;  // queries of the current block
 
-    // B-operand fragments of block j straight from global memory into the registers that hold them (column = query
-    // r, contraction = channels 16*kc + 8g ..: lane (r, g) reads every second 16-byte chunk of its own query row;
-    // rows past the end repeat the last one).  Issued while the previous block's last tile and output are still
-    // in progress - the old fragments are dead after that tile's first contraction - so the round trip is hidden.
-    auto load_query_fragments = [&](int j) {
+    // B-operand fragments of block j of item `it` straight from global memory into the registers that hold them
+    // (column = query r, contraction = channels 16*kc + 8g ..: lane (r, g) reads every second 16-byte chunk of its own
+    // query row; rows past the end repeat the last one).  Issued while the previous block's last tile and output are
+    // still in progress - the old fragments are dead after that tile's first contraction - so the round trip is hidden.
+    auto load_query_fragments = [&](const BandItem& it, int j) {
         int lane_w = lane;
         asm volatile("" : "+v"(lane_w));  // address arithmetic in place, not kept in registers across the key loop
-        const int rows = n - KT * j < KT ? n - KT * j : KT;
+        const int rows = it.n - KT * j < KT ? it.n - KT * j : KT;
         const int rq = (lane_w & 31) < rows ? (lane_w & 31) : rows - 1;
-        const bf16_t* src = (const bf16_t*)p.q + ((row0 + (int64_t)KT * j + rq) * p.H + h) * D + 8 * (lane_w >> 5);
+        const bf16_t* src = (const bf16_t*)p.q + ((it.row0 + (int64_t)KT * j + rq) * p.H + it.h) * D + 8 * (lane_w >> 5);
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) qf[kc] = *(const bf16x8*)(src + 16 * kc);
     };
@@ -174,7 +207,7 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     // (16 lanes x 16 bytes each), 16 rows at a time through the wave's LDS slot (16-byte chunks of a row XOR-swizzled
     // by the row).  (Stores of 32-byte pieces straight from registers were measured: 2.1 ms against 2.0 ms at the
     // bench size, and 2.9 ms with the non-temporal hint.)
-    auto write_block = [&](int j) {
+    auto write_block = [&](const BandItem& it, int j) {
         int lane_w = lane;
         asm volatile("" : "+v"(lane_w));  // address arithmetic in place, not kept in registers across the key loop
         const int r = lane_w & 31, g = lane_w >> 5;
@@ -182,10 +215,10 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
         char* const slot = lds + SM::SLOTS + cw * SM::SLOT;
         const float l_tot = halves_sum(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const int64_t grow = row0 + (int64_t)KT * j;  // first row of the block in the packed tensors
+        const int64_t grow = it.row0 + (int64_t)KT * j;  // first row of the block in the packed tensors
         if (p.lse && g == 0 && r < nq)
-            p.lse[(int64_t)h * p.total_q + grow + r] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
-        bf16_t* obase = (bf16_t*)p.o + grow * hd + (int64_t)h * D;
+            p.lse[(int64_t)it.h * p.total_q + grow + r] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * (1.f / LOG2E) : -INFINITY;
+        bf16_t* obase = (bf16_t*)p.o + grow * hd + (int64_t)it.h * D;
         constexpr int O_STORES = 16 * CHUNKS / 64;
         const int chunk = lane_w % CHUNKS, rsub = lane_w / CHUNKS;
 #pragma unroll
@@ -210,17 +243,20 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the slot has been read before the other half overwrites it
         }
     };
-    // one key tile of the current block; LAST: the block's last tile - the next block's query fragments are requested
-    // as soon as this tile's first contraction has consumed the current ones
-    auto tile_step = [&](int jc, int s, bool last) {
-        // tile s has landed?  (lane 0 polls, the branch is uniform)
+    // One key tile of the current block: tile s of the item, number T0 + s of the workgroup's stream.  On the block's
+    // last tile the query fragments of the wave's next block (`pre_it`, `pre_j`; pre_j < 0: none) are requested as
+    // soon as this tile's first contraction has consumed the current ones.
+    auto tile_step = [&](const BandItem& it, int T0, int jc, int s, const BandItem& pre_it, int pre_j) {
+        const int n = it.n;
+        const int gs = T0 + s;
+        // tile gs has landed?  (lane 0 polls, the branch is uniform)
         for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
             const int landed = __builtin_amdgcn_readfirstlane(flags[0]);
-            if (landed > s) break;
+            if (landed > gs) break;
             __builtin_amdgcn_s_sleep(1);
         }
         asm volatile("" ::: "memory");  // the tile reads below stay behind the poll
-        const char* st = lds + (s % SM::R) * SM::STAGE;
+        const char* st = lds + (gs % SM::R) * SM::STAGE;
         // ---- S^T = K Q^T
         f32x16 sacc;
 #pragma unroll
@@ -230,7 +266,7 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
             const bf16x8 a = *(const bf16x8*)(st + (k_rd ^ (kc << 5)));
             sacc = mfma32(a, qf[kc], sacc);
         }
-        if (last && jc + NWC < NB) load_query_fragments(jc + NWC);
+        if (pre_j >= 0) load_query_fragments(pre_it, pre_j);
         // ---- online softmax; only tiles that some query of the block sees partly take the masked path
         const int key_base = s * KT;
         const int tq_lo = KT * jc, tq_hi = KT * jc + nq - 1;
@@ -253,39 +289,62 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
                 oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
             }
         }
-        // every LDS read of tile s has been issued (the LDS serves a wave's operations in order, and the empty
+        // every LDS read of the tile has been issued (the LDS serves a wave's operations in order, and the empty
         // statement keeps the compiler from moving the store up): publish
         asm volatile("" ::: "memory");
-        if (lane == 0) flags[1 + cw] = s + 1;
+        if (lane == 0) flags[1 + cw] = gs + 1;
     };
 
-    // this wave's blocks: cw, cw + NWC, ...
-    if (cw < NB) load_query_fragments(cw);
-    for (int jc = cw; jc < NB; jc += NWC) {
-        const int fj = plan.first(jc), ej = plan.last(jc);
-        // from here on this wave reads no tile before fj
-        if (lane == 0) flags[1 + cw] = fj;
+    int T0 = 0;             // stream number of the current item's first tile
+    bool q_ready = false;   // the fragments of this wave's first block of the current item were requested during the item before
+    BandItem cur, nxt;
+    bool have = describe(0, cur);
+    for (int k = 0; have; ++k) {
+        const bool have_nxt = describe(k + 1, nxt);
+        if (cur.n > 0) {
+            const int n = cur.n;
+            BandPlan plan;
+            plan.n = n; plan.left = p.left; plan.right = p.right; plan.n_tiles = (n + KT - 1) / KT;
+            const int NB = plan.n_tiles;  // query blocks = key tiles
+            // this wave's blocks: cw, cw + NWC, ...
+            if (cw < NB && !q_ready) load_query_fragments(cur, cw);
+            q_ready = false;
+            for (int jc = cw; jc < NB; jc += NWC) {
+                const int fj = plan.first(jc), ej = plan.last(jc);
+                // from here on this wave reads no tile before fj
+                if (lane == 0) flags[1 + cw] = T0 + fj;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[db][0][v] = 0.f;
-        m_ref = -INFINITY; l_run = 0.f;
-        nq = n - KT * jc;
-        nq = nq > KT ? KT : nq;
-        {
-            const int tq = KT * jc + r;  // this lane's query (inside the sequence)
-            int lo = tq - p.left, hi = n - 1;
-            lo = lo > 0 ? lo : 0;
-            if ((int64_t)tq + p.right < hi) hi = tq + p.right;
-            const bool empty = hi < lo || r >= nq;
-            key_lo = empty ? 0x3fffffff : lo;
-            key_span = empty ? 0u : (unsigned)(hi - lo);
+                    for (int v = 0; v < 16; ++v) oacc[db][0][v] = 0.f;
+                m_ref = -INFINITY; l_run = 0.f;
+                nq = n - KT * jc;
+                nq = nq > KT ? KT : nq;
+                {
+                    const int tq = KT * jc + r;  // this lane's query (inside the sequence)
+                    int lo = tq - p.left, hi = n - 1;
+                    lo = lo > 0 ? lo : 0;
+                    if ((int64_t)tq + p.right < hi) hi = tq + p.right;
+                    const bool empty = hi < lo || r >= nq;
+                    key_lo = empty ? 0x3fffffff : lo;
+                    key_span = empty ? 0u : (unsigned)(hi - lo);
+                }
+                for (int s = fj; s < ej; ++s) tile_step(cur, T0, jc, s, cur, -1);
+                // the block after this one: in this item, else the wave's first block of the next item (if it has one)
+                const bool same = jc + NWC < NB;
+                q_ready = !same && have_nxt && nxt.n > KT * cw;
+                const BandItem pre = same ? cur : nxt;
+                tile_step(cur, T0, jc, ej, pre, same ? jc + NWC : (q_ready ? cw : -1));
+                write_block(cur, jc);
+            }
+            T0 += NB;
+            // done with this item: this wave holds back none of its stages
+            if (lane == 0) flags[1 + cw] = T0;
         }
-        for (int s = fj; s < ej; ++s) tile_step(jc, s, false);
-        tile_step(jc, ej, true);
-        write_block(jc);
+        cur = nxt;
+        have = have_nxt;
     }
-    // no further block: this wave holds back no stage
+    // no further item
     if (lane == 0) flags[1 + cw] = 0x7fffffff;
 }
 
@@ -316,8 +375,10 @@ static hipError_t launch_band(const AttnParams& p, hipStream_t stream) {
         static const hipError_t raised = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (raised != hipSuccess) return raised;
     }
-    const unsigned grid = (unsigned)((((int64_t)p.B + 7) / 8) * 8 * p.H);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * (NWC + 1)), bytes, stream, p);
+    const int64_t n_items = (((int64_t)p.B + 7) / 8) * 8 * p.H;
+    const int64_t resident = compute_units();  // one workgroup (all of the LDS) per compute unit
+    const unsigned grid = (unsigned)(n_items < resident ? n_items : resident);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * (NWC + 1)), bytes, stream, p, (int)n_items);
     return hipGetLastError();
 }
 
