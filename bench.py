@@ -38,7 +38,7 @@ ORACLE_SAMPLE_EXAMPLES = 256
 # profiles/bench_cfg4_hbm_traffic.txt.  Valid for the default workload and seed only.  (The
 # counters sit between L2 and the memory fabric: re-reads that the 256 MB Infinity Cache serves
 # are included, which is what the sliding-window figure above its algorithmic 9.38 GB shows.)
-MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4957134000, "gdpa_bwd": 9780146000, "swa_fwd": 9376853000}
+MEASURED_TRAFFIC_BYTES = {"gdpa_fwd": 4958000000, "gdpa_bwd": 9782000000, "swa_fwd": 9377000000}
 
 
 def device_normal(torch, shape, sigma, seed):
