@@ -333,6 +333,24 @@ def main():
                           "pct_mfma_peak": round(100 * fl / (tw * 1e-6) / MFMA_BF16_PEAK, 2)}
         other["diagnostic_mfma_bound_gdpa_fwd_Nq512"] = diag
 
+        # Seed-level attention with batch-shared seeds (Sec. "Hierarchical Seed Pooling", stage 1: S = 256 learnable
+        # seeds attend to every history under softmax) on the bench batch: forward, and backward with the seed
+        # gradient summed over the batch in fixed order.
+        n_seeds = 256
+        e_seed = device_normal(torch, (n_seeds, H, d), r["sigma"], 31 + args.seed)
+        do_s = device_normal(torch, (B * n_seeds, H, d), 1.0, 32 + args.seed)
+        o_se = torch.empty((B * n_seeds, H, d), dtype=torch.bfloat16, device="cuda")
+        lse_se = torch.empty((H, B * n_seeds), dtype=torch.float32, device="cuda")
+        ws_sf = torch.empty(kb.workspace_bytes(kb.OP_SEED_FWD, B, H, d, n_seeds, max_kv, B * n_seeds, T), dtype=torch.uint8, device="cuda")
+        ws_sb = torch.empty(kb.workspace_bytes(kb.OP_SEED_BWD, B, H, d, n_seeds, max_kv, B * n_seeds, T), dtype=torch.uint8, device="cuda")
+        tf_, _ = timed(lambda: kb.seed_attn_fwd(e_seed, k, v, off, scale_swa, max_kv=max_kv, out=o_se, lse=lse_se, workspace=ws_sf), n=5)
+        tb_, _ = timed(lambda: kb.seed_attn_bwd(e_seed, k, v, do_s, off, scale_swa, o=o_se, lse=lse_se, max_kv=max_kv, workspace=ws_sb), n=3)
+        fl_f, fl_b = W.gdpa_flops(H, d, n_seeds, T), W.gdpa_flops(H, d, n_seeds, T, backward=True)
+        other["seed_attention_256_shared_seeds_bench_batch"] = {
+            "fwd_ms": round(tf_ / 1e3, 3), "fwd_tflops": round(fl_f / tf_ / 1e6, 1), "fwd_pct_mfma_peak": round(100 * fl_f / (tf_ * 1e-6) / MFMA_BF16_PEAK, 2),
+            "bwd_ms": round(tb_ / 1e3, 3), "bwd_tflops": round(fl_b / tb_ / 1e6, 1), "bwd_pct_mfma_peak": round(100 * fl_b / (tb_ * 1e-6) / MFMA_BF16_PEAK, 2)}
+        del e_seed, do_s, o_se, lse_se, ws_sf, ws_sb
+
         # Measured speed of light of this device, by library routines of the harness (torch): a 1 GiB
         # device-to-device copy (read + write) and a large bf16 GEMM.
         # What this memory system sustains depends on the read : write mix of a stream, so the calls
