@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkunlun.so")
-SOURCES = ["api.hip", "static_scratch.hip", "sched.hip", "stream_probe.hip", "scalar_kernels.hip", "attn_fwd_mfma.hip", "attn_fwd_ring_mfma.hip", "attn_swa_band_mfma.hip", "attn_bwd_mfma.hip", "attn_bwd_pair_mfma.hip", "attn_bwd_tiled_mfma.hip", "sumkron.hip"]
+SOURCES = ["api.hip", "static_scratch.hip", "sched.hip", "stream_probe.hip", "scalar_kernels.hip", "attn_fwd_mfma.hip", "attn_fwd_ring_mfma.hip", "attn_swa_band_mfma.hip", "attn_bwd_mfma.hip", "attn_bwd_pair_mfma.hip", "attn_bwd_tiled_mfma.hip", "sumkron.hip", "sumkron_fused.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

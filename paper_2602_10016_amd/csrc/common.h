@@ -98,6 +98,11 @@ hipError_t launch_mfma_bwd_tiled(const AttnParams& p, void* workspace_tail, bool
 
 // SumKronLinear (two tiled GEMMs with a bf16 intermediate, or plain fp32 kernels)
 size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype);
+// One-kernel forward for T = 32, S in {128, 256}, D in {128, 256, 384}, k <= 8 (sumkron_fused.hip)
+bool sumkron_fused_supported(int S, int T, int D, int k, int dtype);
+size_t sumkron_fused_workspace(int S, int T, int D, int k);
+hipError_t launch_sumkron_fused(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k, void* workspace,
+                                hipStream_t stream);
 hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
                           int dtype, void* workspace, hipStream_t stream);
 bool sumkron_bwd_tiled_supported(int B, int S, int T, int D, int k, int dtype);

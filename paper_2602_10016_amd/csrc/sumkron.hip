@@ -351,6 +351,7 @@ bool sumkron_bwd_tiled_supported(int B, int S, int T, int D, int k, int dtype) {
 }
 
 size_t sumkron_workspace(int B, int S, int T, int D, int k, int dtype) {
+    if (sumkron_fused_supported(S, T, D, k, dtype)) return sumkron_fused_workspace(S, T, D, k);
     if (sumkron_tiled_supported(S, T, D, k, dtype))
         return align_up((size_t)k * T * S * 2, 256) + align_up((size_t)B * T * k * D * 2, 256);
     return align_up((size_t)B * T * k * D * sizeof(double), 256);
@@ -414,6 +415,7 @@ static void launch_stage1(const bf16_t* x, const bf16_t* z, bf16_t* zt, bf16_t* 
 
 hipError_t launch_sumkron(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,
                           int dtype, void* workspace, hipStream_t stream) {
+    if (sumkron_fused_supported(S, T, D, k, dtype)) return launch_sumkron_fused(x, z, w, y, B, S, T, D, k, workspace, stream);
     if (sumkron_tiled_supported(S, T, D, k, dtype)) {
         bf16_t* zt = (bf16_t*)workspace;
         bf16_t* u = (bf16_t*)((char*)workspace + align_up((size_t)k * T * S * 2, 256));
