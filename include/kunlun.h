@@ -224,8 +224,10 @@ size_t kunlun_workspace_bytes(int op, int B, int H, int d, int max_q, int max_kv
  *   y  out, device, [B, T, D]   fully overwritten
  * all row-major, contiguous, `dtype` elements, 16-byte aligned.  KUNLUN_BF16: both contractions on
  * the matrix cores with fp32 accumulation when D is a multiple of 128 and S a multiple of 32 (the
- * intermediate Z_i^T X_b is rounded to bf16 once); other shapes and KUNLUN_FP32 take plain fp32
- * kernels.  workspace: device, at least kunlun_sumkron_workspace_bytes(...) bytes, 256-byte aligned.
+ * intermediate Z_i^T X_b is rounded to bf16 once) - in ONE kernel that keeps the intermediate on the
+ * compute unit when T = 32, S is 128 or 256, D <= 384 and k <= 8 (the paper's S = 256, T = 32, D = 384,
+ * k = 8 among them), else as two matrix products through the workspace; other shapes and KUNLUN_FP32
+ * take plain kernels that keep every intermediate and sum in fp64.  workspace: device, at least kunlun_sumkron_workspace_bytes(...) bytes, 256-byte aligned.
  * B == 0 is legal and does nothing.  Errors as for the other entry points.
  */
 int kunlun_sumkron_fwd(const void* x, const void* z, const void* w, void* y, int B, int S, int T, int D, int k,

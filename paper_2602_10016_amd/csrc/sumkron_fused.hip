@@ -185,24 +185,34 @@ __global__ __launch_bounds__(64 * SKF_WAVES, 1) void sumkron_fused_kernel(const 
                     for (int j = 0; j < NBW; ++j) dst[j] = *(const bf16x8*)(src + j * 4 * 512);
                     asm volatile("" ::: "memory");
                 };
-                auto compute = [&](int i, int f, const bf16x8 (&wa)[NBW]) {
-                    const bf16x8 ub = *(const bf16x8*)(ldsU + (((es * 8 + i) * 4 + f) * FRAG) + lane * 16);
+                // the U^T fragment of step (i, f): requested two steps ahead of its use
+                bf16x8 ubq[4];
+                auto fetch_u = [&](int i, int f, bf16x8& dst) {
+                    dst = *(const bf16x8*)(ldsU + (((es * 8 + i) * 4 + f) * FRAG) + lane * 16);
+                };
+                auto compute = [&](const bf16x8& ub, const bf16x8 (&wa)[NBW]) {
 #pragma unroll
                     for (int j = 0; j < NBW; ++j) yacc[j] = mfma32(wa[j], ub, yacc[j]);
                 };
                 issue(0, 0, wq[0]);
                 issue(0, 1, wq[1]);
                 issue(0, 2, wq[2]);
+                fetch_u(0, 0, ubq[0]);
+                fetch_u(0, 1, ubq[1]);
                 for (int i = 0; i < k; ++i) {
                     const int in = i + 1 < k ? i + 1 : i;  // (past the last factor: its fragments once more, unused)
                     issue(i, 3, wq[3]);
-                    compute(i, 0, wq[0]);
+                    fetch_u(i, 2, ubq[2]);
+                    compute(ubq[0], wq[0]);
                     issue(in, 0, wq[0]);
-                    compute(i, 1, wq[1]);
+                    fetch_u(i, 3, ubq[3]);
+                    compute(ubq[1], wq[1]);
                     issue(in, 1, wq[1]);
-                    compute(i, 2, wq[2]);
+                    fetch_u(in, 0, ubq[0]);
+                    compute(ubq[2], wq[2]);
                     issue(in, 2, wq[2]);
-                    compute(i, 3, wq[3]);
+                    fetch_u(in, 1, ubq[1]);
+                    compute(ubq[3], wq[3]);
                 }
             }
             {   // the X blocks of the step after the next: requested last, so that no wait for a W fragment covers them
