@@ -122,8 +122,13 @@ def test_sumkron_argument_validation_without_gpu(kb):
     assert call(z=0x1004) == kb.ERR_ALIGN
     assert call(ws=None) == kb.ERR_WORKSPACE and call(n=16) == kb.ERR_WORKSPACE
     assert call(ws=0x1010) == kb.ERR_ALIGN
+    # the paper's shape runs as one kernel: the workspace holds the prepared copies of Z and W, nothing per example
     need = kb.sumkron_workspace_bytes(1024, 256, 32, 384, 8)
-    assert need >= 1024 * 32 * 8 * 384 * 2 and kb.sumkron_workspace_bytes(4, 0, 1, 8, 1) == 0
+    assert 8 * 32 * 256 * 2 + 8 * 384 * 384 * 2 <= need < 1024 * 32 * 8 * 384 * 2
+    assert kb.sumkron_workspace_bytes(1, 256, 32, 384, 8) == need
+    # two-GEMM shapes (T != 32 here): the transposed Z and the bf16 intermediate of every example
+    assert kb.sumkron_workspace_bytes(1024, 256, 16, 384, 8) >= 1024 * 16 * 8 * 384 * 2
+    assert kb.sumkron_workspace_bytes(4, 0, 1, 8, 1) == 0
 
 
 def test_sumkron_bwd_argument_validation_without_gpu(kb):
