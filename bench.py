@@ -246,6 +246,21 @@ def main():
         t = timed(lambda: kb.gdpa_bwd(q2, k2, v2, do2, off2, w2.scale, act, max_q=w2.Nq, max_kv=1024, workspace=wsx))
         other["cfg5_gdpa_bwd"] = entry(*t, W.gdpa_bytes(w2.H, w2.d, w2.total_q, w2.total_kv, backward=True),
                                        W.gdpa_flops(w2.H, w2.d, w2.Nq, w2.total_kv, backward=True))
+        # the same bytes moved without arithmetic: one walk per (example, head) over the cfg2 histories (best launch
+        # width of 1, 2, 4 workgroups per compute unit), and a flat sweep over contiguous buffers of the same size
+        dk2, dv2 = torch.empty_like(k2), torch.empty_like(v2)
+        kv_bytes2 = 2 * k2.numel() * 2
+        flat_a = torch.empty(kv_bytes2, dtype=torch.uint8, device="cuda")
+        flat_b = torch.empty_like(flat_a)
+        for key, nr, nw, oa, ob in (("cfg2_gdpa_fwd", 2, 0, None, None), ("cfg5_gdpa_bwd", 2, 2, dk2, dv2)):
+            walk = min((timed(lambda: kb.jagged_stream_probe(k2, v2, None, oa, ob, off2, 1024, nr, nw, wg, workspace=wsx), n=10)
+                        for wg in (1, 2, 4)), key=lambda t: t[1])
+            flat = timed(lambda: kb.stream_probe(flat_a, None, None, flat_b, 1, 1 if nw else 0), n=10)
+            other[key]["byte_moving_walk_us"] = round(walk[1], 1)
+            other[key]["byte_moving_walk_us_warm"] = round(walk[0], 1)
+            other[key]["flat_sweep_same_bytes_us"] = round(flat[1], 1)
+            other[key]["kernel_vs_walk"] = round(walk[1] / other[key]["us"], 3)
+        del dk2, dv2, flat_a, flat_b
         w3 = W.make("cfg3", args.seed)
         q3, k3, v3 = dev(w3.q), dev(w3.k), dev(w3.v)
         off3 = torch.from_numpy(w3.kv_offsets).cuda()
