@@ -107,16 +107,27 @@ namespace kunlun {
 // ---- gradient of batch-shared seed queries (Sec. "Hierarchical Seed Pooling", stage 1: the learnable seeds are
 // shared by all examples, so their gradient is the sum of the per-example query gradients).  No atomics: the
 // order of every addition is fixed by (group, example), so the result does not depend on the launch.
-template <typename T>
+// V consecutive elements per thread (16-byte loads when the row length allows it); the additions of one element
+// happen in example order whatever V is.
+template <typename T, int V>
 __global__ __launch_bounds__(256) void seed_grad_group_kernel(const T* __restrict__ rows, float* __restrict__ partial, int B,
                                                               int64_t n_elems) {
-    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    typedef T vec_t __attribute__((ext_vector_type(V)));
+    const int64_t n = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V;
     const int group = blockIdx.y;
     if (n >= n_elems) return;
     const int b0 = group * SEED_GROUP, b1 = b0 + SEED_GROUP < B ? b0 + SEED_GROUP : B;
-    float acc = 0.f;
-    for (int b = b0; b < b1; ++b) acc += to_float(rows[(int64_t)b * n_elems + n]);
-    partial[(int64_t)group * n_elems + n] = acc;
+    float acc[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) acc[q] = 0.f;
+#pragma unroll 4
+    for (int b = b0; b < b1; ++b) {
+        const vec_t x = *(const vec_t*)(rows + (int64_t)b * n_elems + n);
+#pragma unroll
+        for (int q = 0; q < V; ++q) acc[q] += to_float((T)x[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < V; ++q) partial[(int64_t)group * n_elems + n + q] = acc[q];
 }
 template <typename T>
 __global__ __launch_bounds__(256) void seed_grad_final_kernel(const float* __restrict__ partial, T* __restrict__ d_e, int groups,
@@ -131,12 +142,19 @@ __global__ __launch_bounds__(256) void seed_grad_final_kernel(const float* __res
 hipError_t launch_seed_grad_sum(const void* rows, void* d_e, float* partial, int B, int64_t n_elems, int dtype, hipStream_t stream) {
     if (n_elems <= 0) return hipSuccess;
     const int groups = (B + SEED_GROUP - 1) / SEED_GROUP;
-    const dim3 grid1((unsigned)((n_elems + 255) / 256), (unsigned)groups), grid2((unsigned)((n_elems + 255) / 256));
+    const dim3 grid2((unsigned)((n_elems + 255) / 256));
+    auto grid1 = [&](int v) { return dim3((unsigned)((n_elems / v + 255) / 256), (unsigned)groups); };
     if (dtype == KUNLUN_FP32) {
-        hipLaunchKernelGGL(seed_grad_group_kernel<float>, grid1, dim3(256), 0, stream, (const float*)rows, partial, B, n_elems);
+        if (n_elems % 4 == 0 && (reinterpret_cast<uintptr_t>(rows) % 16 == 0))
+            hipLaunchKernelGGL((seed_grad_group_kernel<float, 4>), grid1(4), dim3(256), 0, stream, (const float*)rows, partial, B, n_elems);
+        else
+            hipLaunchKernelGGL((seed_grad_group_kernel<float, 1>), grid1(1), dim3(256), 0, stream, (const float*)rows, partial, B, n_elems);
         hipLaunchKernelGGL(seed_grad_final_kernel<float>, grid2, dim3(256), 0, stream, partial, (float*)d_e, groups, n_elems);
     } else {
-        hipLaunchKernelGGL(seed_grad_group_kernel<bf16_t>, grid1, dim3(256), 0, stream, (const bf16_t*)rows, partial, B, n_elems);
+        if (n_elems % 8 == 0 && (reinterpret_cast<uintptr_t>(rows) % 16 == 0))
+            hipLaunchKernelGGL((seed_grad_group_kernel<bf16_t, 8>), grid1(8), dim3(256), 0, stream, (const bf16_t*)rows, partial, B, n_elems);
+        else
+            hipLaunchKernelGGL((seed_grad_group_kernel<bf16_t, 1>), grid1(1), dim3(256), 0, stream, (const bf16_t*)rows, partial, B, n_elems);
         hipLaunchKernelGGL(seed_grad_final_kernel<bf16_t>, grid2, dim3(256), 0, stream, partial, (bf16_t*)d_e, groups, n_elems);
     }
     return hipGetLastError();
