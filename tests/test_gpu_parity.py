@@ -402,12 +402,13 @@ def test_sumkron_forward_tiled(kb, oracle, B, S, T, D, k):
     assert_close(to_np(y), oracle.sumkron_fwd(x, z, w), TOL["bf16"], f"sumkron B={B} S={S} T={T} D={D} k={k}")
 
 
-@pytest.mark.parametrize("B,S,T,D,k", [(5, 256, 32, 384, 8),     # the paper's typical configuration; a last pair of one example
+@pytest.mark.parametrize("B,S,T,D,k", [(5, 256, 32, 384, 8),     # the paper's typical configuration; a last group of one example
                                        (4, 256, 32, 384, 8),
+                                       (7, 256, 32, 384, 7),     # three examples in the last group, an odd number of factors
                                        (1, 256, 32, 128, 1),     # one example, one factor, two channel blocks
                                        (3, 128, 32, 256, 3),     # the shorter X; waves without a factor
                                        (6, 128, 32, 256, 5),     # an odd number of factors: the two halves differ
-                                       (601, 128, 32, 128, 2)])  # more pairs than compute units: several pairs per workgroup
+                                       (1101, 128, 32, 128, 2)]) # more groups of four than compute units: several groups per workgroup
 def test_sumkron_forward_fused(kb, oracle, B, S, T, D, k):
     """bf16, T = 32, S in {128, 256}, D in {128, 256, 384}, k <= 8: one kernel, Z^T X stays on the compute unit (rounded to
     bf16 once, as in the two-GEMM path).  Every output element against the oracle."""
@@ -419,8 +420,8 @@ def test_sumkron_forward_fused(kb, oracle, B, S, T, D, k):
 
 
 def test_sumkron_fused_paper_shape_large_batch(kb, oracle):
-    """The paper's shape with more pairs of examples than compute units (a workgroup takes several pairs, the X blocks of
-    the next pair are requested during the last steps of the current one): sampled examples against the oracle (examples
+    """The paper's shape with more groups of four examples than compute units (a workgroup takes several groups, the X blocks
+    of the next group are on their way during the last step of the current one): sampled examples against the oracle (examples
     are independent), every output row written."""
     B, S, T, D, k = 1100, 256, 32, 384, 8
     x, z, w = _sumkron_inputs(171, B, S, T, D, k, "bf16")
@@ -438,7 +439,7 @@ def test_sumkron_fused_examples_are_isolated_and_repeatable(kb):
     xd, zd, wd = to_dev(x, "bf16"), to_dev(z, "bf16"), to_dev(w, "bf16")
     y1 = kb.sumkron_fwd(xd, zd, wd)
     y2 = kb.sumkron_fwd(xd, zd, wd)
-    y3 = kb.sumkron_fwd(xd[3:6].contiguous(), zd, wd)   # other partners in the pairs, same results
+    y3 = kb.sumkron_fwd(xd[3:6].contiguous(), zd, wd)   # other partners in the groups, same results
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)
     assert torch.equal(y1[3:6], y3)
