@@ -121,6 +121,27 @@ __global__ __launch_bounds__(64 * SKF_WAVES, 1) void sumkron_fused_kernel(const 
     send_x(group, 0);
     load_z();
     wait_vmcnt<0>();
+    // W fragments travel three fragment steps ahead of their use in a ring of four register sets that runs on from
+    // one step into the next (W does not depend on the group): the first three steps of all
+    const int kp = (k + 1) & ~1;                                  // factors rounded up to whole pairs
+    constexpr int64_t wfactor = (int64_t)D * D;                   // values per factor
+    constexpr int64_t wblock = (int64_t)(D / 32) * 2 * 512;       // values per channel block of a factor
+    const bf16_t* const wlane = wp + (int64_t)NBW * ng * 2 * 512 + lane * 8;
+    bf16x8 wq[4][NBW];
+    auto issue = [&](int cb, int i, int cc, bf16x8 (&dst)[NBW]) {
+        // factor i of block cb; i >= kp: factor i - kp of the next block (past the last real factor: it once more, unused)
+        const bool next = i >= kp;
+        int ii = next ? i - kp : i;
+        ii = ii < k ? ii : k - 1;
+        const int cbb = next ? (cb + 1 < NCB ? cb + 1 : 0) : cb;
+        const bf16_t* src = wlane + cbb * wblock + ii * wfactor + cc * 512;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) dst[j] = *(const bf16x8*)(src + j * 2 * 512);
+        asm volatile("" ::: "memory");
+    };
+    issue(0, 0, 0, wq[0]);
+    issue(0, 0, 1, wq[1]);
+    issue(0, 1, 0, wq[2]);
     for (; group < n_groups; group += gridDim.x) {
         f32x16 yacc[2][NBW];
 #pragma unroll
@@ -182,16 +203,6 @@ __global__ __launch_bounds__(64 * SKF_WAVES, 1) void sumkron_fused_kernel(const 
             // sinking the loads to their use (it would then wait for every single one).  The Z fragments of the next
             // stage 1 are requested behind the last factor, the X blocks of the step after the next at the very end.
             {
-                const bf16_t* const wbase = wp + (((int64_t)cb * (D / 32) + NBW * ng) * 2) * 512 + lane * 8;
-                constexpr int64_t wfactor = (int64_t)D * D;  // values per factor
-                bf16x8 wq[4][NBW];
-                auto issue = [&](int i, int cc, bf16x8 (&dst)[NBW]) {
-                    i = i < k ? i : k - 1;  // (past the last factor: its fragments once more, unused)
-                    const bf16_t* src = wbase + i * wfactor + cc * 512;
-#pragma unroll
-                    for (int j = 0; j < NBW; ++j) dst[j] = *(const bf16x8*)(src + j * 2 * 512);
-                    asm volatile("" ::: "memory");
-                };
                 // the U^T fragments of both examples for step (i, cc): requested one step ahead of their use
                 bf16x8 ubq[2][2];
                 auto fetch_u = [&](int i, int cc, bf16x8 (&dst)[2]) {
@@ -206,27 +217,26 @@ __global__ __launch_bounds__(64 * SKF_WAVES, 1) void sumkron_fused_kernel(const 
                         yacc[1][j] = mfma32(wa[j], ub[1], yacc[1][j]);
                     }
                 };
-                issue(0, 0, wq[0]);
-                issue(0, 1, wq[1]);
-                issue(1, 0, wq[2]);
                 fetch_u(0, 0, ubq[0]);
                 for (int i0 = 0; i0 < k; i0 += 2) {
                     const bool two = i0 + 1 < k;
-                    issue(i0 + 1, 1, wq[3]);
+                    issue(cb, i0 + 1, 1, wq[3]);
                     fetch_u(i0, 1, ubq[1]);
                     compute(ubq[0], wq[0]);
-                    issue(i0 + 2, 0, wq[0]);
+                    issue(cb, i0 + 2, 0, wq[0]);
                     fetch_u(i0 + 1, 0, ubq[0]);
                     compute(ubq[1], wq[1]);
-                    issue(i0 + 2, 1, wq[1]);
+                    issue(cb, i0 + 2, 1, wq[1]);
                     fetch_u(i0 + 1, 1, ubq[1]);
                     if (two) compute(ubq[0], wq[2]);
-                    issue(i0 + 3, 0, wq[2]);
+                    issue(cb, i0 + 3, 0, wq[2]);
                     fetch_u(i0 + 2, 0, ubq[0]);
                     if (two) compute(ubq[1], wq[3]);
                 }
             }
-            wait_vmcnt<0>();  // the X blocks have landed (and the unused last W fragments)
+            // the X blocks have landed: they are older than every W fragment, and at most the three fragment steps
+            // requested for the next block are still on their way
+            wait_vmcnt<3 * NBW>();
         }
         // ---- output: lane holds column t = r of Y^T, rows n = 32*(NBW*ng + j) + 8*(v/4) + 4g + v%4
 #pragma unroll
