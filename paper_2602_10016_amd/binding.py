@@ -121,6 +121,26 @@ def _on_device(**tensors):
             raise ValueError(f"{name}: on {t.device}, expected {dev}")
 
 
+# The operators trust their offsets and the length bounds max_q / max_kv / max_len (an under-estimate selects a kernel
+# whose tiles are too small).  With KUNLUN_CHECK_OFFSETS=1 in the environment - or verify_offsets(True) - every call
+# first runs kunlun_check_offsets on its offsets (one small kernel and a synchronising read per call: a debugging mode).
+VERIFY_OFFSETS = os.environ.get("KUNLUN_CHECK_OFFSETS", "0") == "1"
+
+
+def verify_offsets(on: bool = True) -> None:
+    global VERIFY_OFFSETS
+    VERIFY_OFFSETS = bool(on)
+
+
+def _verify(name, offsets, total, max_len, stream):
+    if not VERIFY_OFFSETS or offsets is None:
+        return
+    bad = check_offsets(offsets, total, max_len, stream=stream)
+    if bad:
+        raise ValueError(f"{name}: {bad} violation(s) of the contract offsets[0] = 0, 0 <= length <= {int(max_len)}, "
+                         f"offsets[-1] = {int(total)}")
+
+
 def _check_qkv(q, k, v):
     if not isinstance(q, torch.Tensor) or q.dim() != 3:
         raise ValueError("q: expected a [rows, H, d] tensor")
@@ -189,6 +209,8 @@ def gdpa_fwd(q, k, v, kv_offsets, scale, act, *, q_offsets=None, max_q=None, max
     ha = _head_act(head_act, H)
     ws = _workspace(workspace, nbytes, q.device)
     _on_device(q=q, k=k, v=v, kv_offsets=kv_offsets, q_offsets=q_offsets, out=o, lse=lse, workspace=ws)
+    _verify("kv_offsets", kv_offsets, total_kv, max_kv, stream)
+    _verify("q_offsets", q_offsets, total_q, max_q, stream)
     rc = _lib.kunlun_gdpa_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(q_offsets), _ptr(kv_offsets), B, H,
                               d, int(max_q), int(max_kv), total_q, total_kv, float(scale), int(act), ha,
                               _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
@@ -210,6 +232,8 @@ def gdpa_fwd_static(q, k, v, kv_offsets, scale, act, *, out, lse=None, q_offsets
     _check("lse", lse, dtype=torch.float32, shape=(H, total_q), optional=True)
     ha = _head_act(head_act, H)
     _on_device(q=q, k=k, v=v, kv_offsets=kv_offsets, q_offsets=q_offsets, out=out, lse=lse)
+    _verify("kv_offsets", kv_offsets, k.shape[0], max_kv, stream)
+    _verify("q_offsets", q_offsets, q.shape[0], max_q, stream)
     rc = _lib.kunlun_gdpa_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(q_offsets), _ptr(kv_offsets), B, H,
                                      d, int(max_q), int(max_kv), total_q, k.shape[0], float(scale), int(act), ha,
                                      _dtype_code(q), _stream(stream))
@@ -249,6 +273,8 @@ def gdpa_bwd(q, k, v, d_o, kv_offsets, scale, act, *, o=None, lse=None, q_offset
     ws = _workspace(workspace, nbytes, q.device)
     _on_device(q=q, k=k, v=v, d_o=d_o, o=o, lse=lse, kv_offsets=kv_offsets, q_offsets=q_offsets, dq=dq, dk=dk, dv=dv,
                workspace=ws)
+    _verify("kv_offsets", kv_offsets, total_kv, max_kv, stream)
+    _verify("q_offsets", q_offsets, total_q, max_q, stream)
     rc = _lib.kunlun_gdpa_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
                               _ptr(q_offsets), _ptr(kv_offsets), B, H, d, int(max_q), int(max_kv), total_q, total_kv,
                               float(scale), int(act), ha, _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))
@@ -273,6 +299,7 @@ def seed_attn_fwd(e_seed, k, v, kv_offsets, scale, act=ACT_SOFTMAX, *, max_kv, h
     ha = _head_act(head_act, H)
     ws = _workspace(workspace, workspace_bytes(OP_SEED_FWD, B, H, d, n_seeds, max_kv, total_q, k.shape[0]), e_seed.device)
     _on_device(e_seed=e_seed, k=k, v=v, kv_offsets=kv_offsets, out=o, lse=lse, workspace=ws)
+    _verify("kv_offsets", kv_offsets, k.shape[0], max_kv, stream)
     rc = _lib.kunlun_seed_attn_fwd(_ptr(e_seed), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(kv_offsets), B, H, d, n_seeds,
                                    int(max_kv), k.shape[0], float(scale), int(act), ha, _dtype_code(e_seed), _ptr(ws), ws.numel(),
                                    _stream(stream))
@@ -296,6 +323,7 @@ def seed_attn_bwd(e_seed, k, v, d_o, kv_offsets, scale, act=ACT_SOFTMAX, *, o=No
     ha = _head_act(head_act, H)
     ws = _workspace(workspace, workspace_bytes(OP_SEED_BWD, B, H, d, n_seeds, max_kv, total_q, k.shape[0]), e_seed.device)
     _on_device(e_seed=e_seed, k=k, v=v, d_o=d_o, o=o, lse=lse, kv_offsets=kv_offsets, d_e=d_e, dk=dk, dv=dv, workspace=ws)
+    _verify("kv_offsets", kv_offsets, k.shape[0], max_kv, stream)
     rc = _lib.kunlun_seed_attn_bwd(_ptr(e_seed), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_e), _ptr(dk), _ptr(dv),
                                    _ptr(kv_offsets), B, H, d, n_seeds, int(max_kv), k.shape[0], float(scale), int(act), ha,
                                    _dtype_code(e_seed), _ptr(ws), ws.numel(), _stream(stream))
@@ -321,6 +349,7 @@ def swa_fwd(q, k, v, offsets, window_left, window_right, scale, *, max_len, out=
     nbytes = workspace_bytes(OP_SWA_FWD, B, H, d, max_len, max_len, total, total)
     ws = _workspace(workspace, nbytes, q.device)
     _on_device(q=q, k=k, v=v, offsets=offsets, out=o, lse=lse, workspace=ws)
+    _verify("offsets", offsets, total, max_len, stream)
     rc = _lib.kunlun_swa_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(offsets), B, H, d, int(max_len),
                              total, int(window_left), int(window_right), float(scale), _dtype_code(q), _ptr(ws),
                              ws.numel(), _stream(stream))
@@ -346,6 +375,7 @@ def swa_bwd(q, k, v, o, lse, d_o, offsets, window_left, window_right, scale, *, 
     nbytes = workspace_bytes(OP_SWA_BWD, B, H, d, max_len, max_len, total, total)
     ws = _workspace(workspace, nbytes, q.device)
     _on_device(q=q, k=k, v=v, o=o, lse=lse, d_o=d_o, offsets=offsets, dq=dq, dk=dk, dv=dv, workspace=ws)
+    _verify("offsets", offsets, q.shape[0], max_len, stream)
     rc = _lib.kunlun_swa_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
                              _ptr(offsets), B, H, d, int(max_len), total, int(window_left), int(window_right),
                              float(scale), _dtype_code(q), _ptr(ws), ws.numel(), _stream(stream))

@@ -175,3 +175,22 @@ def test_many_more_examples_than_scheduler_threads(kb, oracle):
     """B = 5000 short examples: the sorting kernel and the prefix kernel walk several examples per thread."""
     fwd_case(kb, oracle, 5000, 1, 64, 8, 0, 40, 3, seed=77)
     bwd_case(kb, oracle, 5000, 1, 64, 8, 0, 40, 0, seed=78)
+
+
+def test_offsets_verification_mode_rejects_a_length_above_the_bound(kb):
+    """With verification switched on, the binding runs kunlun_check_offsets before a call: a max_kv below the longest
+    history (which would select kernels by a wrong bound) is refused instead of computed."""
+    wl = W.make("cfg2", 3, B=6, lengths=("uniform", 40, 90))
+    q, k, v = (to_dev(a, "bf16") for a in (wl.q, wl.k, wl.v))
+    off = offsets_dev(wl.kv_offsets)
+    kb.verify_offsets(True)
+    try:
+        kb.gdpa_fwd(q, k, v, off, wl.scale, kb.ACT_GELU, max_q=wl.Nq, max_kv=96)       # a true bound: fine
+        with pytest.raises(ValueError):
+            kb.gdpa_fwd(q, k, v, off, wl.scale, kb.ACT_GELU, max_q=wl.Nq, max_kv=32)   # an under-estimate
+        bad = off.clone()
+        bad[2] = bad[3] + 1                                                             # a negative length
+        with pytest.raises(ValueError):
+            kb.gdpa_fwd(q, k, v, bad, wl.scale, kb.ACT_GELU, max_q=wl.Nq, max_kv=96)
+    finally:
+        kb.verify_offsets(False)
