@@ -189,6 +189,7 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     int key_lo = 0x3fffffff;
     unsigned key_span = 0u;
     int nq = 0;  // queries of the current block
+    int landed = 0;  // tiles of the stream that this wave has seen landed
 
     // B-operand fragments of block j of item `it` straight from global memory into the registers that hold them
     // (column = query r, contraction = channels 16*kc + 8g ..: lane (r, g) reads every second 16-byte chunk of its own
@@ -249,11 +250,14 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     auto tile_step = [&](const BandItem& it, int T0, int jc, int s, const BandItem& pre_it, int pre_j) {
         const int n = it.n;
         const int gs = T0 + s;
-        // tile gs has landed?  (lane 0 polls, the branch is uniform)
-        for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
-            const int landed = __builtin_amdgcn_readfirstlane(flags[0]);
-            if (landed > gs) break;
-            __builtin_amdgcn_s_sleep(1);
+        // tile gs has landed?  (the count last seen is kept: the loader is usually several tiles ahead, and the LDS
+        // round trip of a poll is then saved; the branch is uniform)
+        if (landed <= gs) {
+            for (int spin = 0; spin < BAND_SPIN_LIMIT; ++spin) {
+                landed = __builtin_amdgcn_readfirstlane(flags[0]);
+                if (landed > gs) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
         }
         asm volatile("" ::: "memory");  // the tile reads below stay behind the poll
         const char* st = lds + (gs % SM::R) * SM::STAGE;
