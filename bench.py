@@ -199,14 +199,23 @@ def main():
     # The other the benchmark spec workloads (parity-test cases, small): timed separately, no part of
     # `value`; reported for their achieved HBM GB/s.  Their inputs fit the 256 MB Infinity Cache, so
     # back-to-back launches are warm-cache figures: the primary numbers (us, gbps, tflops) are COLD
-    # (cache flushed by 1 GiB of writes before every launch), the warm ones are given alongside.
+    # (before every launch 1 GiB of unrelated writes, then 1 GiB of reads streamed through: nothing of the
+    # inputs is cached and no write-back of the flush is pending), the warm ones are given alongside, and so
+    # is the figure after the writes alone (`us_after_write_only_flush`: 256 MB of dirty lines are then
+    # written back during the timed launch, which is what earlier figures of these rows contained).
     other = {}
     if not args.skip_other_configs:
         flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")   # 4x the 256 MB Infinity Cache
 
+        sink = torch.empty(4096, dtype=torch.uint8, device="cuda")
+
         def timed(fn, n=20):
-            """(warm, cold) microseconds per call: warm = back-to-back launches, inputs stay in the
-            Infinity Cache; cold = median of single launches, each after 1 GiB of unrelated writes."""
+            """(warm, cold, cold_dirty) microseconds per call.  warm = back-to-back launches (inputs that fit stay in the
+            Infinity Cache).  cold = median of single launches, each after 1 GiB of unrelated writes AND then 1 GiB
+            of reads streamed through (kunlun_stream_probe): nothing of the inputs is cached, and the cache holds clean
+            lines.  cold_dirty = after the 1 GiB of writes only: the Infinity Cache is then full of dirty lines whose
+            write-back (256 MB) lands in the timed region - a property of that flush, not of the kernel; kept because
+            earlier figures were taken this way."""
             for _ in range(3):
                 fn()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -217,19 +226,22 @@ def main():
             b.record()
             torch.cuda.synchronize()
             warm = a.elapsed_time(b) / n
-            cold = []
-            for i in range(7):
+            cold, dirty = [], []
+            for i in range(14):
                 flush.fill_(i)
+                if i % 2 == 0:
+                    kb.stream_probe(flush, None, None, sink, 1, 0)
                 a.record()
                 fn()
                 b.record()
                 torch.cuda.synchronize()
-                cold.append(a.elapsed_time(b))
-            return warm * 1e3, float(np.median(cold)) * 1e3
+                (cold if i % 2 == 0 else dirty).append(a.elapsed_time(b))
+            return warm * 1e3, float(np.median(cold)) * 1e3, float(np.median(dirty)) * 1e3
 
-        def entry(us_warm, us_cold, by, fl):
+        def entry(us_warm, us_cold, us_dirty, by, fl):
             return {"us": round(us_cold, 1), "gbps": round(by / us_cold / 1e3, 1), "tflops": round(fl / us_cold / 1e6, 1),
-                    "us_warm": round(us_warm, 1), "gbps_warm": round(by / us_warm / 1e3, 1)}
+                    "us_warm": round(us_warm, 1), "gbps_warm": round(by / us_warm / 1e3, 1),
+                    "us_after_write_only_flush": round(us_dirty, 1)}
 
         dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).cuda()
         w2 = W.make("cfg2", args.seed)
@@ -319,7 +331,7 @@ def main():
         wk = device_normal(torch, (kk, Dk, Dk), 1.0 / math.sqrt(Dk), 43)
         yk = torch.empty((Bk, Tk, Dk), dtype=torch.bfloat16, device="cuda")
         wsk = torch.empty(kb.sumkron_workspace_bytes(Bk, Sk, Tk, Dk, kk), dtype=torch.uint8, device="cuda")
-        tw, tc = timed(lambda: kb.sumkron_fwd(xk, zk, wk, out=yk, workspace=wsk), n=10)
+        tw, tc, *_ = timed(lambda: kb.sumkron_fwd(xk, zk, wk, out=yk, workspace=wsk), n=10)
         fl = 2.0 * Bk * kk * Tk * Dk * (Sk + Dk)
         other["sumkron_fwd_S256_T32_D384_k8_B1024"] = {"us": round(tc, 1), "us_warm": round(tw, 1), "tflops": round(fl / tc / 1e6, 1),
                                                        "pct_mfma_peak": round(100 * fl / (tc * 1e-6) / MFMA_BF16_PEAK, 2),
@@ -329,7 +341,7 @@ def main():
                                                                "largely out of the 256 MB Infinity Cache"}
         dyk = device_normal(torch, (Bk, Tk, Dk), 1.0, 44)
         wsb = torch.empty(kb.sumkron_bwd_workspace_bytes(Bk, Sk, Tk, Dk, kk), dtype=torch.uint8, device="cuda")
-        tw, tc = timed(lambda: kb.sumkron_bwd(xk, zk, wk, dyk, workspace=wsb), n=10)
+        tw, tc, *_ = timed(lambda: kb.sumkron_bwd(xk, zk, wk, dyk, workspace=wsb), n=10)
         fl = 2.0 * Bk * kk * Tk * Dk * (3 * Sk + 2 * Dk)   # U, G, dX, dW, dZ: each intermediate computed once
         other["sumkron_bwd_S256_T32_D384_k8_B1024"] = {"us": round(tc, 1), "us_warm": round(tw, 1), "tflops": round(fl / tc / 1e6, 1),
                                                        "pct_mfma_peak": round(100 * fl / (tc * 1e-6) / MFMA_BF16_PEAK, 2)}
@@ -347,7 +359,7 @@ def main():
         fl = W.gdpa_flops(H, d, Nd, Bd * Ld)
         diag = {}
         for name, a, sc_ in (("gelu", act, 1.0 / Ld), ("softmax", kb.ACT_SOFTMAX, 1.0 / math.sqrt(d))):
-            tw, _ = timed(lambda: kb.gdpa_fwd(qd, kd, vd, offd, sc_, a, max_q=Nd, max_kv=Ld, out=od, want_lse=False, workspace=wsx), n=10)
+            tw, *_ = timed(lambda: kb.gdpa_fwd(qd, kd, vd, offd, sc_, a, max_q=Nd, max_kv=Ld, out=od, want_lse=False, workspace=wsx), n=10)
             diag[name] = {"us": round(tw, 1), "tflops": round(fl / tw / 1e6, 1),
                           "pct_mfma_peak": round(100 * fl / (tw * 1e-6) / MFMA_BF16_PEAK, 2)}
         other["diagnostic_mfma_bound_gdpa_fwd_Nq512"] = diag
@@ -362,8 +374,8 @@ def main():
         lse_se = torch.empty((H, B * n_seeds), dtype=torch.float32, device="cuda")
         ws_sf = torch.empty(kb.workspace_bytes(kb.OP_SEED_FWD, B, H, d, n_seeds, max_kv, B * n_seeds, T), dtype=torch.uint8, device="cuda")
         ws_sb = torch.empty(kb.workspace_bytes(kb.OP_SEED_BWD, B, H, d, n_seeds, max_kv, B * n_seeds, T), dtype=torch.uint8, device="cuda")
-        tf_, _ = timed(lambda: kb.seed_attn_fwd(e_seed, k, v, off, scale_swa, max_kv=max_kv, out=o_se, lse=lse_se, workspace=ws_sf), n=5)
-        tb_, _ = timed(lambda: kb.seed_attn_bwd(e_seed, k, v, do_s, off, scale_swa, o=o_se, lse=lse_se, max_kv=max_kv, workspace=ws_sb), n=3)
+        tf_, *_ = timed(lambda: kb.seed_attn_fwd(e_seed, k, v, off, scale_swa, max_kv=max_kv, out=o_se, lse=lse_se, workspace=ws_sf), n=5)
+        tb_, *_ = timed(lambda: kb.seed_attn_bwd(e_seed, k, v, do_s, off, scale_swa, o=o_se, lse=lse_se, max_kv=max_kv, workspace=ws_sb), n=3)
         fl_f, fl_b = W.gdpa_flops(H, d, n_seeds, T), W.gdpa_flops(H, d, n_seeds, T, backward=True)
         other["seed_attention_256_shared_seeds_bench_batch"] = {
             "fwd_ms": round(tf_ / 1e3, 3), "fwd_tflops": round(fl_f / tf_ / 1e6, 1), "fwd_pct_mfma_peak": round(100 * fl_f / (tf_ * 1e-6) / MFMA_BF16_PEAK, 2),
@@ -376,19 +388,19 @@ def main():
         # are put next to plain streaming kernels of their own mix (1 GiB fp32 operands): a sum (reads
         # only, like gdpa_fwd), a copy (1 : 1, like gdpa_bwd), a + b * c (3 reads : 1 write, like swa_fwd).
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        tw, _ = timed(lambda: flush.copy_(src), n=10)
+        tw, *_ = timed(lambda: flush.copy_(src), n=10)
         fa, fb = src.view(torch.float32), flush.view(torch.float32)
         fc, fd = torch.ones_like(fa), torch.empty_like(fa)
-        t31, _ = timed(lambda: torch.addcmul(fa, fb, fc, out=fd), n=10)
-        tr, _ = timed(lambda: torch.sum(fa), n=10)
+        t31, *_ = timed(lambda: torch.addcmul(fa, fb, fc, out=fd), n=10)
+        tr, *_ = timed(lambda: torch.sum(fa), n=10)
         ga = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
         gb = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
-        tg, _ = timed(lambda: torch.matmul(ga, gb), n=10)
+        tg, *_ = timed(lambda: torch.matmul(ga, gb), n=10)
         # the same three mixes by the library's own plain streaming kernel (kunlun_stream_probe: 16 KB per
         # workgroup and stream, non-temporal), the best of the access patterns tried on this device
         probe = {}
         for name, reads, write in (("read_only", 3, 0), ("one_read_one_write", 1, 1), ("three_reads_one_write", 3, 1)):
-            tp, _ = timed(lambda: kb.stream_probe(src, flush, fc.view(torch.uint8), fd.view(torch.uint8), reads, write), n=10)
+            tp, *_ = timed(lambda: kb.stream_probe(src, flush, fc.view(torch.uint8), fd.view(torch.uint8), reads, write), n=10)
             probe[name + "_gbps"] = round((reads + write) * (1 << 30) / tp / 1e3, 1)
         other["device_calibration"] = {"stream_probe_1GiB_operands": probe,
                                        "torch_sum_1GiB_gbps": round((1 << 30) / tr / 1e3, 1),
