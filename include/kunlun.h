@@ -76,15 +76,24 @@ typedef enum {
 
 typedef enum { KUNLUN_BF16 = 0, KUNLUN_FP32 = 1 } kunlun_dtype;
 
-/* Score functions.  gelu(x) = x * Phi(x) (erf form); gelu_tanh is the tanh approximation
- * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))); silu(x) = x / (1 + exp(-x)). */
+/* Score functions (Eq. (GDPA): one activation per head).  gelu(x) = x * Phi(x) (erf form); gelu_tanh is the
+ * tanh approximation 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))); silu(x) = x / (1 + exp(-x)).
+ * gelu_poly is a GELU without a transcendental (App. "GDPA and Fused PFFN Kernel": without softmax the
+ * special-function unit becomes the limiter, to be relieved by plain arithmetic), DEFINED as
+ *     gelu_poly(x) = x * (1/2 + t q(t^2)),   t = min(max(x, -C), C),   C = 3.875,
+ *     q(u) = 3.9862210505e-01 - 6.5595134356e-02 u + 9.2376422360e-03 u^2 - 9.1053389233e-04 u^3
+ *            + 5.8010079080e-05 u^4 - 2.1110704002e-06 u^5 + 3.2949778488e-08 u^6
+ * (C q(C^2) = 1/2: exactly 0 below -C, exactly x above C).  |gelu_poly(x) - gelu(x)| <= 3e-4 and
+ * |gelu_poly(x) / x - Phi(x)| <= 8e-5 for every x: below the bf16 rounding of any weight above 0.15.  Its
+ * derivative is that of this function (1/2 + t q + x (q + 2 t^2 q') inside (-C, C); 0 or 1 outside). */
 typedef enum {
     KUNLUN_ACT_SOFTMAX = 0,
     KUNLUN_ACT_IDENTITY = 1,
     KUNLUN_ACT_RELU = 2,
     KUNLUN_ACT_GELU = 3,
     KUNLUN_ACT_GELU_TANH = 4,
-    KUNLUN_ACT_SILU = 5
+    KUNLUN_ACT_SILU = 5,
+    KUNLUN_ACT_GELU_POLY = 6
 } kunlun_act;
 
 typedef enum {

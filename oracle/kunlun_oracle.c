@@ -42,11 +42,31 @@
 #include <omp.h>
 #endif
 
-enum { ACT_SOFTMAX = 0, ACT_IDENTITY = 1, ACT_RELU = 2, ACT_GELU = 3, ACT_GELU_TANH = 4, ACT_SILU = 5 };
+enum { ACT_SOFTMAX = 0, ACT_IDENTITY = 1, ACT_RELU = 2, ACT_GELU = 3, ACT_GELU_TANH = 4, ACT_SILU = 5, ACT_GELU_POLY = 6 };
 
 static const double SQRT_2_OVER_PI = 0.79788456080286535587989211986876;
 static const double INV_SQRT_2 = 0.70710678118654752440084436210485;
 static const double INV_SQRT_2PI = 0.39894228040143267793994605993438;
+
+/* The polynomial GELU (a score function without a transcendental, after the remark of App. "GDPA and Fused
+ * PFFN Kernel" that without softmax the special-function unit limits the kernel):
+ *     gelu_poly(x) = x * cdf(x),  cdf(x) = 1/2 + t * q(t^2),  t = x clamped to [-C, C],  q of degree 6.
+ * The coefficients ARE the definition of this score function (they are an odd near-minimax fit of Phi - 1/2
+ * on [-C, C] under the side condition C q(C^2) = 1/2, so that the tails are exactly 0 and exactly x);
+ * the pins hold it within 8e-5 of Phi and 3e-4 of x Phi(x). */
+static const double GELU_POLY_C = 3.875;
+static const double GELU_POLY_Q[7] = {3.9862210505e-01,  -6.5595134356e-02, 9.2376422360e-03, -9.1053389233e-04,
+                                      5.8010079080e-05,  -2.1110704002e-06, 3.2949778488e-08};
+/* cdf(x) of the polynomial GELU and its derivative (0 outside [-C, C]). */
+static double gelu_poly_cdf(double x, double* slope) {
+    const double t = x < -GELU_POLY_C ? -GELU_POLY_C : (x > GELU_POLY_C ? GELU_POLY_C : x);
+    const double u = t * t;
+    double q = 0.0, dq = 0.0; /* q(u) and q'(u) */
+    for (int i = 6; i >= 0; --i) q = q * u + GELU_POLY_Q[i];
+    for (int i = 6; i >= 1; --i) dq = dq * u + i * GELU_POLY_Q[i];
+    *slope = (x > -GELU_POLY_C && x < GELU_POLY_C) ? q + 2.0 * u * dq : 0.0;
+    return 0.5 + t * q;
+}
 
 /* Element-wise score functions, exact definitions. */
 static double act_value(int act, double x) {
@@ -59,6 +79,10 @@ static double act_value(int act, double x) {
         return 0.5 * x * (1.0 + tanh(u));
     }
     case ACT_SILU: return x / (1.0 + exp(-x));
+    case ACT_GELU_POLY: {
+        double slope;
+        return x * gelu_poly_cdf(x, &slope);
+    }
     default: return NAN;
     }
 }
@@ -82,6 +106,11 @@ static double act_deriv(int act, double x) {
     case ACT_SILU: {
         double s = 1.0 / (1.0 + exp(-x));
         return s + x * s * (1.0 - s);
+    }
+    case ACT_GELU_POLY: {
+        double slope;
+        const double cdf = gelu_poly_cdf(x, &slope);
+        return cdf + x * slope;
     }
     default: return NAN;
     }
@@ -121,7 +150,7 @@ static int attention_forward(const double* q, const double* k, const double* v, 
                              int left, int right) {
     for (int h = 0; h < H; ++h) {
         int a = head_activation(act, head_act, h);
-        if (a < ACT_SOFTMAX || a > ACT_SILU) return -1;
+        if (a < ACT_SOFTMAX || a > ACT_GELU_POLY) return -1;
     }
     const int64_t hd = (int64_t)H * d;
     int64_t max_kv = 1;
@@ -196,7 +225,7 @@ static int attention_backward(const double* q, const double* k, const double* v,
                               const int32_t* head_act, int windowed, int left, int right) {
     for (int h = 0; h < H; ++h) {
         int a = head_activation(act, head_act, h);
-        if (a < ACT_SOFTMAX || a > ACT_SILU) return -1;
+        if (a < ACT_SOFTMAX || a > ACT_GELU_POLY) return -1;
     }
     const int64_t hd = (int64_t)H * d;
     memset(dq, 0, sizeof(double) * (size_t)(total_q * hd));

@@ -26,6 +26,11 @@ MUTANTS = [
     ("gelu_tanh_coefficient", "double u = SQRT_2_OVER_PI * (x + 0.044715 * x * x * x);\n        return 0.5 * x",
      "double u = SQRT_2_OVER_PI * (x + 0.44715 * x * x * x);\n        return 0.5 * x", 0),
     ("gelu_derivative_drops_pdf_term", "return cdf + x * pdf;", "return cdf;", 0),
+    ("gelu_poly_coefficient_sign", "9.2376422360e-03, -9.1053389233e-04,", "9.2376422360e-03, 9.1053389233e-04,", 0),
+    ("gelu_poly_not_clamped", "(x > GELU_POLY_C ? GELU_POLY_C : x);", "(x > GELU_POLY_C ? x : x);", 0),
+    ("gelu_poly_slope_drops_chain_term", "? q + 2.0 * u * dq : 0.0;", "? q : 0.0;", 0),
+    ("gelu_poly_slope_not_zero_outside", "(x > -GELU_POLY_C && x < GELU_POLY_C) ? q + 2.0 * u * dq : 0.0;",
+     "q + 2.0 * u * dq;", 0),
     ("backward_scores_not_scaled", "s[j] = scale * dot;", "s[j] = dot;", 1),
     ("softmax_backward_drops_delta", "p[j] * (dp[j] - delta) * scale", "p[j] * dp[j] * scale", 0),
     ("activation_backward_drops_scale", ": dp[j] * act_deriv(a, s[j]) * scale;", ": dp[j] * act_deriv(a, s[j]);", 0),
@@ -62,6 +67,9 @@ def _battery():
         calls.append((pins.test_activation_values_vs_libraries, dict(x=x)))
         for name in ("gelu", "gelu_tanh", "silu"):
             calls.append((pins.test_activation_derivatives_vs_autograd, dict(name=name, x=x)))
+    calls.append((pins.test_polynomial_gelu_tracks_gelu_and_has_exact_tails, {}))
+    for x in (-4.0, -1.2, 0.4, 3.3):
+        calls.append((pins.test_activation_derivatives_vs_autograd, dict(name="gelu_poly", x=x)))
     calls.append((pins.test_lse_consistency, {}))
     calls.append((pins.test_softmax_special_cases, {}))
     calls.append((pins.test_window_special_cases, {}))

@@ -21,7 +21,18 @@ import torch
 
 from paper_2602_10016_amd import workloads as W
 
-ACTS = {"softmax": 0, "identity": 1, "relu": 2, "gelu": 3, "gelu_tanh": 4, "silu": 5}
+ACTS = {"softmax": 0, "identity": 1, "relu": 2, "gelu": 3, "gelu_tanh": 4, "silu": 5, "gelu_poly": 6}
+# the polynomial GELU of include/kunlun.h: x * (1/2 + t q(t^2)), t = x clamped to [-C, C]
+GELU_POLY_C = 3.875
+GELU_POLY_Q = [3.9862210505e-01, -6.5595134356e-02, 9.2376422360e-03, -9.1053389233e-04, 5.8010079080e-05,
+               -2.1110704002e-06, 3.2949778488e-08]
+
+
+def torch_gelu_poly(z):
+    t = torch.clamp(z, -GELU_POLY_C, GELU_POLY_C)
+    u = t * t
+    q = sum(c * u ** i for i, c in enumerate(GELU_POLY_Q))
+    return z * (0.5 + t * q)
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_worked.txt")
 
 
@@ -38,6 +49,9 @@ def np_act(name, x):
         return 0.5 * x * (1 + np.tanh(math.sqrt(2 / math.pi) * (x + 0.044715 * x ** 3)))
     if name == "silu":
         return x * scipy.special.expit(x)
+    if name == "gelu_poly":
+        t = np.clip(x, -GELU_POLY_C, GELU_POLY_C)
+        return x * (0.5 + t * np.polynomial.polynomial.polyval(t * t, GELU_POLY_Q))
     raise KeyError(name)
 
 
@@ -118,13 +132,39 @@ def test_activation_values_vs_libraries(oracle, x):
     assert oracle.act_value(ACTS["identity"], x) == x
 
 
-@pytest.mark.parametrize("name", ["identity", "relu", "gelu", "gelu_tanh", "silu"])
+def test_polynomial_gelu_tracks_gelu_and_has_exact_tails(oracle):
+    """The polynomial GELU is a score function of its own (its coefficients define it); what ties it to GELU is
+    the bound stated with its definition: within 8e-5 of Phi in the cdf and 3.1e-4 of x Phi(x) in the value,
+    0 below -C and x above C.  A wrong coefficient, sign or clamp breaks the bound."""
+    xs = np.linspace(-12.0, 12.0, 48001)
+    val = np.array([oracle.act_value(ACTS["gelu_poly"], float(x)) for x in xs])
+    exact = xs * scipy.stats.norm.cdf(xs)
+    assert np.max(np.abs(val - exact)) <= 3.1e-4
+    inside = np.abs(xs) > 1e-3
+    assert np.max(np.abs(val[inside] / xs[inside] - scipy.stats.norm.cdf(xs[inside]))) <= 8e-5
+    # not simply GELU again: the fit's error is really there
+    assert np.max(np.abs(val - exact)) >= 1e-4
+    lo, hi = xs <= -GELU_POLY_C, xs >= GELU_POLY_C
+    assert np.max(np.abs(val[lo])) <= 1e-9 and np.max(np.abs(val[hi] - xs[hi])) <= 1e-9
+    assert oracle.act_value(ACTS["gelu_poly"], 0.0) == 0.0
+    # odd part: value(x) - value(-x) = x, as for GELU (cdf(x) + cdf(-x) = 1)
+    for x in (0.3, 1.7, 3.2, 5.0):
+        assert oracle.act_value(ACTS["gelu_poly"], x) - oracle.act_value(ACTS["gelu_poly"], -x) == pytest.approx(x, abs=1e-9)
+    # the derivative is that of GELU within the fit's slope error, and 0 / 1 in the tails
+    for x in np.linspace(-3.8, 3.8, 77):
+        g = scipy.stats.norm.cdf(x) + x * scipy.stats.norm.pdf(x)
+        assert abs(oracle.act_deriv(ACTS["gelu_poly"], float(x)) - g) <= 4e-3
+    assert oracle.act_deriv(ACTS["gelu_poly"], -4.0) == pytest.approx(0.0, abs=1e-9)
+    assert oracle.act_deriv(ACTS["gelu_poly"], 4.0) == pytest.approx(1.0, abs=1e-9)
+
+
+@pytest.mark.parametrize("name", ["identity", "relu", "gelu", "gelu_tanh", "silu", "gelu_poly"])
 @pytest.mark.parametrize("x", [-4.0, -1.2, -0.1, 0.4, 1.0, 3.3])
 def test_activation_derivatives_vs_autograd(oracle, name, x):
     t = torch.tensor(x, dtype=torch.float64, requires_grad=True)
     f = {"identity": lambda z: z, "relu": torch.relu, "gelu": torch.nn.functional.gelu,
          "gelu_tanh": lambda z: torch.nn.functional.gelu(z, approximate="tanh"),
-         "silu": torch.nn.functional.silu}[name]
+         "silu": torch.nn.functional.silu, "gelu_poly": torch_gelu_poly}[name]
     f(t).backward()
     assert oracle.act_deriv(ACTS[name], x) == pytest.approx(t.grad.item(), rel=1e-12, abs=1e-14)
 
@@ -229,7 +269,7 @@ def test_softmax_special_cases(oracle):
 def test_activation_zero_cases(oracle):
     rng = np.random.default_rng(8)
     q, k, v, q_off, kv_off = rand_problem(rng, [2, 2], [4, 7], 2, 3)
-    for act in ["gelu", "gelu_tanh", "silu", "relu", "identity"]:
+    for act in ["gelu", "gelu_tanh", "silu", "relu", "identity", "gelu_poly"]:
         o, _ = oracle.gdpa_fwd(q, np.zeros_like(k), v, kv_off, 1.0, ACTS[act], max_q=2)
         assert np.all(o == 0.0), act
     # relu with every score negative: k = -q direction
@@ -302,7 +342,7 @@ def test_dense_equal_lengths_match_library_attention_and_autograd(oracle):
     np.testing.assert_allclose(dv, back(tv.grad, L), rtol=1e-11, atol=1e-12)
 
 
-@pytest.mark.parametrize("act", ["identity", "relu", "gelu", "gelu_tanh", "silu"])
+@pytest.mark.parametrize("act", ["identity", "relu", "gelu", "gelu_tanh", "silu", "gelu_poly"])
 def test_activation_mode_backward_vs_autograd(oracle, act):
     """Jagged, per example: torch fp64 autograd through library activations."""
     rng = np.random.default_rng(13)
@@ -312,7 +352,7 @@ def test_activation_mode_backward_vs_autograd(oracle, act):
     scale = 0.45
     f = {"identity": lambda z: z, "relu": torch.relu, "gelu": torch.nn.functional.gelu,
          "gelu_tanh": lambda z: torch.nn.functional.gelu(z, approximate="tanh"),
-         "silu": torch.nn.functional.silu}[act]
+         "silu": torch.nn.functional.silu, "gelu_poly": torch_gelu_poly}[act]
     dq, dk, dv = oracle.gdpa_bwd(q, k, v, d_o, kv_off, scale, ACTS[act], q_offsets=q_off)
     for b in range(3):
         qs, ks = slice(q_off[b], q_off[b + 1]), slice(kv_off[b], kv_off[b + 1])
