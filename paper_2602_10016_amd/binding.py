@@ -19,7 +19,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_ALIGN, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 BF16, FP32 = 0, 1
-ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU = range(6)
+ACT_SOFTMAX, ACT_IDENTITY, ACT_RELU, ACT_GELU, ACT_GELU_TANH, ACT_SILU, ACT_GELU_POLY = range(7)
 OP_GDPA_FWD, OP_GDPA_BWD, OP_SWA_FWD, OP_SWA_BWD, OP_SEED_FWD, OP_SEED_BWD = 0, 1, 2, 3, 4, 5
 EXPORTS = ["kunlun_gdpa_fwd", "kunlun_gdpa_fwd_static", "kunlun_gdpa_bwd", "kunlun_seed_attn_fwd", "kunlun_seed_attn_bwd", "kunlun_swa_fwd", "kunlun_swa_bwd", "kunlun_workspace_bytes",
            "kunlun_sumkron_fwd", "kunlun_sumkron_workspace_bytes", "kunlun_sumkron_bwd", "kunlun_sumkron_bwd_workspace_bytes",

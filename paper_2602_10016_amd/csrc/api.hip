@@ -29,7 +29,7 @@ int fill_acts(AttnParams& p, int H, int act, const int32_t* head_act, bool& any_
     any_softmax = false;
     for (int h = 0; h < H; ++h) {
         const int a = head_act ? head_act[h] : act;
-        if (a < KUNLUN_ACT_SOFTMAX || a > KUNLUN_ACT_SILU) return KUNLUN_ERR_UNSUPPORTED;
+        if (a < KUNLUN_ACT_SOFTMAX || a > KUNLUN_ACT_GELU_POLY) return KUNLUN_ERR_UNSUPPORTED;
         p.head_act[h] = (uint8_t)a;
         any_softmax |= a == KUNLUN_ACT_SOFTMAX;
     }

@@ -364,7 +364,8 @@ __global__ __launch_bounds__(256, 2) void gdpa_bwd_pair_kernel(AttnParams p, int
                 case KUNLUN_ACT_RELU: attn_bwd_pair_item<KUNLUN_ACT_RELU>(p, smem, h, q0, nq, k0, n_kv); break;
                 case KUNLUN_ACT_GELU: attn_bwd_pair_item<KUNLUN_ACT_GELU>(p, smem, h, q0, nq, k0, n_kv); break;
                 case KUNLUN_ACT_GELU_TANH: attn_bwd_pair_item<KUNLUN_ACT_GELU_TANH>(p, smem, h, q0, nq, k0, n_kv); break;
-                default: attn_bwd_pair_item<KUNLUN_ACT_SILU>(p, smem, h, q0, nq, k0, n_kv); break;
+                case KUNLUN_ACT_SILU: attn_bwd_pair_item<KUNLUN_ACT_SILU>(p, smem, h, q0, nq, k0, n_kv); break;
+                default: attn_bwd_pair_item<KUNLUN_ACT_GELU_POLY>(p, smem, h, q0, nq, k0, n_kv); break;
                 }
             }
         }

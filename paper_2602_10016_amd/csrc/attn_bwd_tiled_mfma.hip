@@ -123,7 +123,8 @@ struct UFrag {
     case KUNLUN_ACT_RELU: { constexpr int A = KUNLUN_ACT_RELU; CALL; } break;           \
     case KUNLUN_ACT_GELU: { constexpr int A = KUNLUN_ACT_GELU; CALL; } break;           \
     case KUNLUN_ACT_GELU_TANH: { constexpr int A = KUNLUN_ACT_GELU_TANH; CALL; } break; \
-    default: { constexpr int A = KUNLUN_ACT_SILU; CALL; } break;                        \
+    case KUNLUN_ACT_SILU: { constexpr int A = KUNLUN_ACT_SILU; CALL; } break;                        \
+    default: { constexpr int A = KUNLUN_ACT_GELU_POLY; CALL; } break;                        \
     }
 
 // ------------------------------------------------------------------ pass A: dQ

@@ -369,7 +369,8 @@ __device__ __forceinline__ void attn_fwd_dispatch(const AttnParams& p, char* lds
     case KUNLUN_ACT_RELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_RELU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
     case KUNLUN_ACT_GELU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
     case KUNLUN_ACT_GELU_TANH: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_TANH, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
-    default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    case KUNLUN_ACT_SILU: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_SILU, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
+    default: attn_fwd_item<D, NQB, NW, KUNLUN_ACT_GELU_POLY, AHEAD, KS>(p, lds, h, q_row0, nq, k0, n_kv); break;
     }
 }
 

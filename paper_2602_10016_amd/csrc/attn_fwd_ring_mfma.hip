@@ -252,7 +252,8 @@ __global__ __launch_bounds__(64 * NW, OCC) void qtile_fwd_mfma_kernel(AttnParams
         case KUNLUN_ACT_RELU: attn_fwd_ring_item<D, NW, KUNLUN_ACT_RELU, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
         case KUNLUN_ACT_GELU: attn_fwd_ring_item<D, NW, KUNLUN_ACT_GELU, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
         case KUNLUN_ACT_GELU_TANH: attn_fwd_ring_item<D, NW, KUNLUN_ACT_GELU_TANH, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
-        default: attn_fwd_ring_item<D, NW, KUNLUN_ACT_SILU, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
+        case KUNLUN_ACT_SILU: attn_fwd_ring_item<D, NW, KUNLUN_ACT_SILU, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
+        default: attn_fwd_ring_item<D, NW, KUNLUN_ACT_GELU_POLY, false>(p, lds, h, q0 + q_first, nq, q_first, k0, n_kv); break;
         }
     }
 }

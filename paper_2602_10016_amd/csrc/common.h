@@ -134,6 +134,29 @@ __device__ __forceinline__ int find_example(const int32_t* off, int B, int64_t r
     return lo;
 }
 
+// The polynomial GELU of include/kunlun.h: cdf(x) = 1/2 + t q(t^2), t = x clamped to [-C, C], and the slope of
+// the cdf (0 outside (-C, C)).  Plain fused multiply-adds, no transcendental (App. "GDPA and Fused PFFN Kernel").
+constexpr float GELU_POLY_C = 3.875f;
+__device__ __forceinline__ float gelu_poly_cdf(float x, float& slope) {
+    constexpr float A0 = 3.9862210505e-01f, A1 = -6.5595134356e-02f, A2 = 9.2376422360e-03f, A3 = -9.1053389233e-04f,
+                    A4 = 5.8010079080e-05f, A5 = -2.1110704002e-06f, A6 = 3.2949778488e-08f;
+    const float t = __builtin_amdgcn_fmed3f(x, -GELU_POLY_C, GELU_POLY_C);
+    const float u = t * t;
+    float q = fmaf(u, A6, A5);
+    q = fmaf(u, q, A4);
+    q = fmaf(u, q, A3);
+    q = fmaf(u, q, A2);
+    q = fmaf(u, q, A1);
+    q = fmaf(u, q, A0);
+    float dq = fmaf(u, 6.f * A6, 5.f * A5);  // q'(u)
+    dq = fmaf(u, dq, 4.f * A4);
+    dq = fmaf(u, dq, 3.f * A3);
+    dq = fmaf(u, dq, 2.f * A2);
+    dq = fmaf(u, dq, A1);
+    slope = (x > -GELU_POLY_C && x < GELU_POLY_C) ? fmaf(2.f * u, dq, q) : 0.f;
+    return fmaf(t, q, 0.5f);
+}
+
 // Exact score functions (fp32 path): definitions as in include/kunlun.h.
 template <int ACT>
 __device__ __forceinline__ float act_exact(float x) {
@@ -145,6 +168,10 @@ __device__ __forceinline__ float act_exact(float x) {
         return 0.5f * x * (1.f + tanhf(u));
     }
     if constexpr (ACT == KUNLUN_ACT_SILU) return x / (1.f + expf(-x));
+    if constexpr (ACT == KUNLUN_ACT_GELU_POLY) {
+        float slope;
+        return x * gelu_poly_cdf(x, slope);
+    }
     return 0.f;
 }
 
@@ -167,6 +194,11 @@ __device__ __forceinline__ float act_deriv_exact(float x) {
         float s = 1.f / (1.f + expf(-x));
         return s + x * s * (1.f - s);
     }
+    if constexpr (ACT == KUNLUN_ACT_GELU_POLY) {
+        float slope;
+        const float cdf = gelu_poly_cdf(x, slope);
+        return fmaf(x, slope, cdf);
+    }
     return 0.f;
 }
 
@@ -176,7 +208,8 @@ __device__ __forceinline__ float act_exact_rt(int act, float x) {
     case KUNLUN_ACT_RELU: return act_exact<KUNLUN_ACT_RELU>(x);
     case KUNLUN_ACT_GELU: return act_exact<KUNLUN_ACT_GELU>(x);
     case KUNLUN_ACT_GELU_TANH: return act_exact<KUNLUN_ACT_GELU_TANH>(x);
-    default: return act_exact<KUNLUN_ACT_SILU>(x);
+    case KUNLUN_ACT_SILU: return act_exact<KUNLUN_ACT_SILU>(x);
+    default: return act_exact<KUNLUN_ACT_GELU_POLY>(x);
     }
 }
 __device__ __forceinline__ float act_deriv_exact_rt(int act, float x) {
@@ -185,7 +218,8 @@ __device__ __forceinline__ float act_deriv_exact_rt(int act, float x) {
     case KUNLUN_ACT_RELU: return act_deriv_exact<KUNLUN_ACT_RELU>(x);
     case KUNLUN_ACT_GELU: return act_deriv_exact<KUNLUN_ACT_GELU>(x);
     case KUNLUN_ACT_GELU_TANH: return act_deriv_exact<KUNLUN_ACT_GELU_TANH>(x);
-    default: return act_deriv_exact<KUNLUN_ACT_SILU>(x);
+    case KUNLUN_ACT_SILU: return act_deriv_exact<KUNLUN_ACT_SILU>(x);
+    default: return act_deriv_exact<KUNLUN_ACT_GELU_POLY>(x);
     }
 }
 

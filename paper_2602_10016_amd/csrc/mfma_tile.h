@@ -223,6 +223,10 @@ __device__ __forceinline__ float act_fast(float x) {
         return x * fast_rcp(1.f + fast_exp2(u2 * -1.4426950408889634f));
     }
     if constexpr (ACT == KUNLUN_ACT_SILU) return x * fast_rcp(1.f + fast_exp2(x * -1.4426950408889634f));
+    if constexpr (ACT == KUNLUN_ACT_GELU_POLY) {
+        float slope;  // (unused here: the compiler drops its arithmetic)
+        return x * gelu_poly_cdf(x, slope);
+    }
     return 0.f;
 }
 
@@ -250,6 +254,12 @@ __device__ __forceinline__ void act_fast_vd(float x, float& val, float& der) {
         const float sg = fast_rcp(1.f + fast_exp2(x * -1.4426950408889634f));
         val = x * sg;
         der = fmaf(x * sg, 1.f - sg, sg);
+    }
+    if constexpr (ACT == KUNLUN_ACT_GELU_POLY) {
+        float slope;
+        const float cdf = gelu_poly_cdf(x, slope);
+        val = x * cdf;
+        der = fmaf(x, slope, cdf);
     }
 }
 

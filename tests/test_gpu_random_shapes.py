@@ -39,7 +39,7 @@ def _draw(seed):
     lens_q[rng.integers(B)] = max_q
     lens_kv = rng.integers(0, max_kv + 1, size=B)
     lens_kv[rng.integers(B)] = max_kv
-    acts = [int(a) for a in rng.integers(0, 6, size=H)]
+    acts = [int(a) for a in rng.integers(0, 7, size=H)]
     q_off, kv_off = W.offsets_from_lengths(lens_q), W.offsets_from_lengths(lens_kv)
     bf = lambda shape, s: W.round_to_bf16((rng.standard_normal(shape) * s).astype(np.float32))
     return dict(B=B, H=H, d=d, max_q=max_q, max_kv=max_kv, jagged_q=jagged_q, q_off=q_off, kv_off=kv_off, acts=acts,
