@@ -22,7 +22,10 @@ constexpr float SOFTMAX_LAZY_LOG2 = 8.f;
 // Key k is visible iff (unsigned)(k - key_lo) <= key_span; rel0 = key_base + 4g - key_lo.
 // need_mask (wave-uniform): some (query, key) pair of the tile is not visible.
 // sc = scale (activation heads) or scale * log2(e) (softmax heads; scale > 0).
-template <int ACT, int DB, int NQB>
+// FRESH: the first tile of a query block under softmax - m_ref = -inf, l_run = 0 and the accumulators hold nothing
+// yet (they need not even be initialised), so the reference simply becomes the tile's maximum and nothing is
+// rescaled; the result is the same, bit for bit, as that of the general path on zeroed accumulators.
+template <int ACT, int DB, int NQB, bool FRESH = false>
 __device__ __forceinline__ void score_to_weights(const f32x16& sacc, bool need_mask, unsigned rel0, unsigned key_span,
                                                  float sc, float& m_ref, float& l_run, f32x16 (&oacc)[DB][NQB], int qb,
                                                  bf16x8 (&pf)[2]) {
@@ -48,7 +51,9 @@ __device__ __forceinline__ void score_to_weights(const f32x16& sacc, bool need_m
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, pv[v]);
         mx = halves_max(mx) * sc;  // the other lane half holds the other 16 keys
         const bool grow = mx > m_ref + SOFTMAX_LAZY_LOG2;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        if (FRESH) {
+            m_ref = mx;
+        } else if (__builtin_amdgcn_ballot_w64(grow) != 0) {
             const float corr = grow ? fast_exp2(m_ref - mx) : 1.f;
             m_ref = grow ? mx : m_ref;
             l_run *= corr;

@@ -28,6 +28,8 @@
 //
 // Per tile and compute wave the arithmetic is that of the other forward kernels (S^T = K Q^T, online softmax
 // in registers, O^T += V^T P^T through transposing LDS reads).
+#include <type_traits>
+
 #include "attn_fwd_score.h"
 #include "lds_ring.h"
 
@@ -247,7 +249,10 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
     // One key tile of the current block: tile s of the item, number T0 + s of the workgroup's stream.  On the block's
     // last tile the query fragments of the wave's next block (`pre_it`, `pre_j`; pre_j < 0: none) are requested as
     // soon as this tile's first contraction has consumed the current ones.
-    auto tile_step = [&](const BandItem& it, int T0, int jc, int s, const BandItem& pre_it, int pre_j) {
+    // `fresh` (std::true_type on the block's first tile): the accumulators are assigned, not added to, and the running
+    // softmax statistics are set, not updated - no zeroing of 64 registers per block, no rescaling of zeros.
+    auto tile_step = [&](const BandItem& it, int T0, int jc, int s, const BandItem& pre_it, int pre_j, auto fresh) {
+        constexpr bool FRESH = decltype(fresh)::value;
         const int n = it.n;
         const int gs = T0 + s;
         // tile gs has landed?  (the count last seen is kept: the loader is usually several tiles ahead, and the LDS
@@ -278,8 +283,8 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
         if (key_base < tq_hi - p.left) need_mask = true;
         if ((int64_t)key_base + KT - 1 > (int64_t)tq_lo + p.right) need_mask = true;
         bf16x8 pf[2];
-        score_to_weights<KUNLUN_ACT_SOFTMAX, DB, 1>(sacc, need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref, l_run,
-                                                    oacc, 0, pf);
+        score_to_weights<KUNLUN_ACT_SOFTMAX, DB, 1, FRESH>(sacc, need_mask, (unsigned)(key_base + 4 * g - key_lo), key_span, sc, m_ref,
+                                                           l_run, oacc, 0, pf);
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
@@ -290,7 +295,14 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
                 const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, src + 8 * SM::ROW));
                 typedef __attribute__((ext_vector_type(8))) short s16x8;
                 const bf16x8 a = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
-                oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
+                if (FRESH && c == 0) {
+                    f32x16 zero;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                    oacc[db][0] = mfma32(a, pf[c], zero);
+                } else {
+                    oacc[db][0] = mfma32(a, pf[c], oacc[db][0]);
+                }
             }
         }
         // every LDS read of the tile has been issued (the LDS serves a wave's operations in order, and the empty
@@ -317,10 +329,6 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
                 const int fj = plan.first(jc), ej = plan.last(jc);
                 // from here on this wave reads no tile before fj
                 if (lane == 0) flags[1 + cw] = T0 + fj;
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[db][0][v] = 0.f;
                 m_ref = -INFINITY; l_run = 0.f;
                 nq = n - KT * jc;
                 nq = nq > KT ? KT : nq;
@@ -333,12 +341,18 @@ __global__ __launch_bounds__(64 * (NWC + 1), 1) void swa_band_fwd_kernel(AttnPar
                     key_lo = empty ? 0x3fffffff : lo;
                     key_span = empty ? 0u : (unsigned)(hi - lo);
                 }
-                for (int s = fj; s < ej; ++s) tile_step(cur, T0, jc, s, cur, -1);
                 // the block after this one: in this item, else the wave's first block of the next item (if it has one)
                 const bool same = jc + NWC < NB;
                 q_ready = !same && have_nxt && nxt.n > KT * cw;
                 const BandItem pre = same ? cur : nxt;
-                tile_step(cur, T0, jc, ej, pre, same ? jc + NWC : (q_ready ? cw : -1));
+                const int pre_j = same ? jc + NWC : (q_ready ? cw : -1);
+                if (fj < ej) {
+                    tile_step(cur, T0, jc, fj, cur, -1, std::true_type{});
+                    for (int s = fj + 1; s < ej; ++s) tile_step(cur, T0, jc, s, cur, -1, std::false_type{});
+                    tile_step(cur, T0, jc, ej, pre, pre_j, std::false_type{});
+                } else {
+                    tile_step(cur, T0, jc, ej, pre, pre_j, std::true_type{});
+                }
                 write_block(cur, jc);
             }
             T0 += NB;
