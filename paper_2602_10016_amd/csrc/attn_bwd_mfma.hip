@@ -169,8 +169,10 @@ __device__ __forceinline__ void attn_bwd_item(const AttnParams& p, char* smem, i
         const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)Vg + kt * tile_bytes), 0, bytes, 0x00020000);
 #pragma unroll
         for (int i = 0; i < L::LOADS; ++i) {
-            ks[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, goff, i * L::ROWS_PER_LOAD * row_bytes, 2);
-            vs[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, goff, i * L::ROWS_PER_LOAD * row_bytes, 2);
+            // (streaming loads, except at D = 32: a row piece is then half a 128-byte line, which a streaming load
+            // fetches whole for one use)
+            ks[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, goff, i * L::ROWS_PER_LOAD * row_bytes, D != 32 ? 2 : 0);
+            vs[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, goff, i * L::ROWS_PER_LOAD * row_bytes, D != 32 ? 2 : 0);
         }
     };
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};

@@ -73,7 +73,10 @@ struct CoopTile {
     // past the end of a history read as zero (and get zero weight later), with no address
     // clamping in the loop.  voffset = the thread's constant offset, soffset = uniform.
     // STREAM: the data is read once by this workgroup and by nobody else (GDPA keys/values):
-    // non-temporal loads keep it from displacing useful lines in the caches.
+    // non-temporal loads keep it from displacing useful lines in the caches.  Not at D = 32: a row piece is then
+    // half a 128-byte line, the other half belongs to the neighbouring head, and a streaming load fetches the
+    // whole line for one use (measured on the bench batch: 2.06 GB fetched against 1.80 GB with plain loads, which
+    // the neighbouring head's workgroup can hit in L2 when it runs on the same XCD; the operands are 1.2 GB).
     template <bool STREAM>
     __device__ __forceinline__ void load(u32x4 (&st)[LOADS], const char* __restrict__ tile_base, int rows_valid) const {
         const int rows = rows_valid < KT ? rows_valid : KT;
@@ -81,7 +84,7 @@ struct CoopTile {
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)tile_base, 0, bytes, 0x00020000);
 #pragma unroll
         for (int i = 0; i < LOADS; ++i)
-            st[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff, i * ROWS_PER_LOAD * row_bytes, STREAM ? 2 : 0);
+            st[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, goff, i * ROWS_PER_LOAD * row_bytes, STREAM && D != 32 ? 2 : 0);
     }
     __device__ __forceinline__ void store(char* ldsK, char* ldsV, const u32x4 (&ks)[LOADS], const u32x4 (&vs)[LOADS]) const {
 #pragma unroll
