@@ -191,3 +191,25 @@ def test_static_scratch_entry_point_validates_on_the_host(kb):
     big = 200_000
     assert kb.workspace_bytes(kb.OP_GDPA_FWD, big, 2, 64, 8, 64, big * 8, 100) > kb.STATIC_SCRATCH_BYTES
     assert call(B=big, total_q=big * 8) == kb.ERR_WORKSPACE
+
+
+def test_polynomial_gelu_coefficients_agree_everywhere():
+    """The polynomial GELU is defined by seven coefficients and a clamp that are written out four times (the ABI
+    header, the HIP kernels, the oracle, the oracle's pins): the copies must be the same numbers."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    read = lambda *p: open(os.path.join(root, *p)).read()
+    num = r"[-+]?\d\.\d{10}e[-+]\d\d"
+    header = read("include", "kunlun.h")
+    h = header[header.index("gelu_poly(x) ="):header.index("(C q(C^2) = 1/2")]
+    from_header = [float(x.replace(" ", "")) for x in re.findall(r"[-+]?\s?" + num[5:], h)]
+    kernels = read("paper_2602_10016_amd", "csrc", "common.h")
+    k = kernels[kernels.index("constexpr float A0"):kernels.index("const float t = __builtin_amdgcn_fmed3f")]
+    from_kernels = [float(x) for x in re.findall(num, k)]
+    oracle_c = read("oracle", "kunlun_oracle.c")
+    o = oracle_c[oracle_c.index("GELU_POLY_Q[7]"):oracle_c.index("/* cdf(x) of the polynomial GELU")]
+    from_oracle = [float(x) for x in re.findall(num, o)]
+    from tests.test_oracle_pins import GELU_POLY_C, GELU_POLY_Q
+    assert len(from_oracle) == 7 and from_oracle == from_kernels == GELU_POLY_Q
+    assert [abs(x) for x in from_header] == [abs(x) for x in from_oracle]  # (the header writes the signs as operators)
+    assert "C = 3.875" in header and "GELU_POLY_C = 3.875f" in kernels and "GELU_POLY_C = 3.875;" in oracle_c and GELU_POLY_C == 3.875
