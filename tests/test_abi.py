@@ -213,3 +213,24 @@ def test_polynomial_gelu_coefficients_agree_everywhere():
     assert len(from_oracle) == 7 and from_oracle == from_kernels == GELU_POLY_Q
     assert [abs(x) for x in from_header] == [abs(x) for x in from_oracle]  # (the header writes the signs as operators)
     assert "C = 3.875" in header and "GELU_POLY_C = 3.875f" in kernels and "GELU_POLY_C = 3.875;" in oracle_c and GELU_POLY_C == 3.875
+
+
+def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
+    """include/kunlun.h compiles as strict C99 (no C++-only construct in the ABI) and a C program linked against the
+    library reaches the host-side argument checks (a negative size: refused before any device is touched)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.join(root, "paper_2602_10016_amd")
+    src = tmp_path / "use_kunlun.c"
+    src.write_text(
+        '#include "kunlun.h"\n#include <stdio.h>\n#include <string.h>\n'
+        "int main(void) {\n"
+        "    if (strlen(kunlun_strerror(KUNLUN_ERR_SHAPE)) == 0) return 2;\n"
+        "    if (kunlun_workspace_bytes(KUNLUN_OP_GDPA_FWD, 4, 2, 64, 8, 100, 32, 400) == 0) return 3;\n"
+        "    return kunlun_gdpa_fwd(0, 0, 0, 0, 0, 0, 0, -1, 1, 64, 1, 1, 0, 0, 1.0f, KUNLUN_ACT_GELU_POLY, 0, KUNLUN_BF16, 0, 0, 0)\n"
+        "               == KUNLUN_ERR_SHAPE ? 0 : 1;\n"
+        "}\n")
+    exe = tmp_path / "use_kunlun"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-lkunlun", f"-Wl,-rpath,{libdir}"], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
