@@ -58,6 +58,7 @@ def test_gdpa_fwd_rejects_bad_arguments(kb):
     assert _fwd(lib, d=512) == kb.ERR_UNSUPPORTED
     assert _fwd(lib, H=65) == kb.ERR_UNSUPPORTED
     assert _fwd(lib, act=9) == kb.ERR_UNSUPPORTED
+    assert _fwd(lib, act=7) == kb.ERR_UNSUPPORTED and _fwd(lib, act=-1) == kb.ERR_UNSUPPORTED  # 0..6 are the score functions
     assert _fwd(lib, dtype=7) == kb.ERR_UNSUPPORTED
     assert _fwd(lib, scale=float("nan")) == kb.ERR_UNSUPPORTED
     assert _fwd(lib, head_act=(ctypes.c_int32 * 2)(3, 17)) == kb.ERR_UNSUPPORTED
